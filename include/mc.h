@@ -1,0 +1,142 @@
+/*
+ * mc.h -- C ABI of libmc: one rank's share of a multi-colour Allreduce step fused with
+ * the SGD update, on one AMD MI355X (gfx950).
+ *
+ * Background (paper: "Efficient Training of Convolutional Neural Nets on Large Distributed
+ * Systems", arXiv 1711.00705).  In data-parallel SGD every worker needs the elementwise sum
+ * of all workers' gradients (Section 3, Algorithm 1).  The k-colour Allreduce (Section 4.2)
+ * cuts the flat gradient payload into k chunks ("colours"), sums each chunk along its own
+ * spanning tree, independently of the others, and a rank that is root or inner node of a
+ * colour's tree adds what arrived from its children to the contributions of its own GPUs.
+ * Each GPU then performs the SGD step with the summed gradient.  This library is that
+ * per-rank arithmetic: P staged contributions, packed from per-layer tensors into the flat
+ * colour-chunked payload, summed per colour in a fixed sequence, fused with the update.
+ *
+ * Conventions
+ *   - Every function returns an int: MC_OK (0) or a negative MC_ERR_* code.  No C++ type,
+ *     exception or torch type crosses this boundary.
+ *   - "device" pointers are HIP device addresses valid on the current device; "host"
+ *     pointers are ordinary process memory.  All element data is IEEE binary32 ("fp32"),
+ *     moved as 32-bit words by pack/unpack and added/multiplied with round-to-nearest-even,
+ *     denormals preserved, no fused multiply-add, in reduce_update.
+ *   - The caller owns every device buffer and the stream.  The library owns only mc_layout
+ *     objects (host tables, plus a small device copy of the offset tables made by
+ *     mc_layout_prepare), from create to destroy.  Host arrays passed in are read during
+ *     the call and never retained.
+ *   - mc_pack / mc_unpack / mc_reduce_update validate their arguments on the host BEFORE
+ *     any launch; on error no output is touched.  On success they enqueue work on `stream`
+ *     (NULL = the default stream) and return without synchronising.
+ *   - A layout is immutable after mc_layout_prepare and may then be used from several host
+ *     threads and streams at once.
+ */
+#ifndef MC_H_
+#define MC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mc_layout mc_layout;        /* opaque */
+
+enum {
+    MC_OK = 0,
+    MC_ERR_INVALID_ARG = -1,   /* NULL where a pointer is required, count out of range, bad order row */
+    MC_ERR_ALIGN = -2,         /* a flat buffer is not 16-byte aligned / a tensor not 4-byte aligned */
+    MC_ERR_OVERLAP = -3,       /* two buffers of one call overlap */
+    MC_ERR_ALLOC = -4,         /* host allocation failed */
+    MC_ERR_HIP = -5            /* a HIP runtime call failed; see mc_last_hip_error() */
+};
+
+#define MC_MAX_P 32                 /* most contributions one call can sum */
+#define MC_COLOUR_ALIGN_ELEMS 256   /* colour chunk length is a multiple of this (1 KiB) */
+
+/* ---- a1: layout --------------------------------------------------------------------
+ * Section 4.2 ("the application payload is split into k chunks"): the payload is the dense
+ * concatenation of the n per-layer tensors in the given order (tensor t occupies flat
+ * elements [off_t, off_t + numel[t]), off_t = numel[0] + ... + numel[t-1], N = off_n), and
+ * colour c owns flat elements [b_c, b_{c+1}) with b_c = min(N, c*C),
+ * C = ceil(N / k) rounded up to MC_COLOUR_ALIGN_ELEMS.  Trailing colours may be empty.
+ *
+ * numel: host, n_tensors entries, each >= 0 (0 = the tensor occupies nothing).
+ * out:   receives the new layout (NULL on failure).  Host-only: touches no GPU.
+ * Errors: MC_ERR_INVALID_ARG (NULL, n_tensors < 1, k_colours < 1, negative numel, or a
+ * total above 2^40 elements), MC_ERR_ALLOC. */
+int mc_layout_create(const int64_t* numel, int32_t n_tensors, int32_t k_colours, mc_layout** out);
+
+/* Frees host tables and any device tables.  NULL is a no-op returning MC_OK. */
+int mc_layout_destroy(mc_layout* L);
+
+/* Uploads the offset tables that pack/unpack kernels read to the CURRENT device (one small
+ * allocation, one synchronous copy; idempotent).  mc_pack / mc_unpack call it themselves on
+ * first use; call it explicitly before capturing a graph or timing.  MC_ERR_HIP on failure. */
+int mc_layout_prepare(mc_layout* L);
+
+/* Queries (host outputs).  N: one int64.  off: n_tensors+1 entries.  b: k_colours+1. */
+int mc_layout_total(const mc_layout* L, int64_t* N);
+int mc_layout_counts(const mc_layout* L, int32_t* n_tensors, int32_t* k_colours);
+int mc_layout_tensor_offsets(const mc_layout* L, int64_t* off);
+int mc_layout_colour_bounds(const mc_layout* L, int64_t* b);
+
+/* ---- a2 / a5: pack and unpack ------------------------------------------------------
+ * The payload handed to the Allreduce is ONE flat buffer (Section 4.2; Section 5.1 quotes
+ * its size), while the framework holds one gradient tensor per layer:
+ *   pack:    flat[off_t + j]   = tensors[t][j]      for every t, j < numel[t]
+ *   unpack:  tensors[t][j]     = flat[off_t + j]
+ * Pure 32-bit word copies: every bit pattern (NaN payloads included) survives.
+ *
+ * tensors: host array of n_tensors device pointers, each 4-byte aligned, each with
+ *          numel[t] readable (pack) / writable (unpack) fp32; entries of zero-length
+ *          tensors are ignored and may be NULL.
+ * flat:    device, N fp32, 16-byte aligned.
+ * Errors: MC_ERR_INVALID_ARG (NULL L / tensors / flat with N > 0 / a NULL entry of a
+ * non-empty tensor), MC_ERR_ALIGN, MC_ERR_OVERLAP (a tensor overlaps flat), MC_ERR_HIP. */
+int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream);
+int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream);
+
+/* ---- a3 + a4: per-colour reduction fused with the SGD update -------------------------
+ * Section 3, Algorithm 1 (intra-node sum, inter-node sum, then SGD on each GPU) and
+ * Section 4.2 (each colour summed separately; summing ranks add the children's buffers to
+ * the local GPU contributions).  For every colour c and every flat element i of colour c:
+ *
+ *     g    = x[o(c,0)][i]                          (start from the first term, not from 0)
+ *     g    = g + x[o(c,q)][i]      for q = 1..P-1  (strictly left to right)
+ *     d    = g + wd * w[i]
+ *     v[i] = mu * v[i] + d
+ *     w[i] = w[i] - lr * v[i]                      (uses the NEW v)
+ *     grad_out[i] = g                              (if grad_out != NULL)
+ *
+ * every operation rounded once to fp32.  The paper gives no update formula ("perform SGD");
+ * this is heavy-ball momentum with L2 decay folded into the gradient, dampening 0.
+ *
+ * contrib:  host array of P device pointers, each N fp32 flat, 16-byte aligned.  By
+ *           convention entries 0..m-1 are the node's own GPU replicas and m..P-1 the tree
+ *           children, so the identity sequence is Algorithm 1's order of summation.
+ * order:    host, k_colours*P int32 row-major; row c is the sequence o(c,.) and must be a
+ *           permutation of 0..P-1.  NULL = identity for every colour.
+ * grad_out: device N fp32 or NULL; weights, momentum: device N fp32, updated in place.
+ * Errors: MC_ERR_INVALID_ARG (NULL, P < 1, P > MC_MAX_P, bad order row), MC_ERR_ALIGN,
+ * MC_ERR_OVERLAP (any two of contrib[*], grad_out, weights, momentum overlap), MC_ERR_HIP. */
+int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P,
+                     const int32_t* order, void* grad_out, void* weights, void* momentum,
+                     float lr, float mu, float wd, void* stream);
+
+/* ---- diagnostics and tuning ---------------------------------------------------------- */
+const char* mc_strerror(int code);     /* static string, never NULL */
+int mc_last_hip_error(void);           /* raw hipError_t of this thread's last MC_ERR_HIP */
+
+/* Launch-shape knobs for measurement sweeps; results never depend on them.
+ * Returns MC_ERR_INVALID_ARG for an unknown option or a value outside its range. */
+enum {
+    MC_OPT_RU_UNROLL = 1,       /* 16-byte vectors per thread per tile in reduce_update: 1, 2 or 4 */
+    MC_OPT_RU_NONTEMPORAL = 2,  /* 1: streaming (non-temporal) loads of contributions and store of grad_out */
+    MC_OPT_RU_BLOCK = 3         /* threads per workgroup in reduce_update: 256 or 512 */
+};
+int mc_set_option(int option, int value);
+int mc_get_option(int option, int* value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MC_H_ */

@@ -1,0 +1,64 @@
+// Internal declarations shared by the translation units of libmc (never installed).
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "mc.h"
+
+namespace mc {
+
+// Elements of the flat payload that one workgroup of the pack / unpack kernels covers.
+constexpr int64_t kPackTileElems = 4096;
+// Device pointers that fit in one pack / unpack launch's kernel-argument block.
+constexpr int kPackMaxPtrs = 256;
+constexpr int kMaxDevices = 16;
+
+struct DeviceTables {
+    bool ready = false;
+    int64_t* off = nullptr;         // n+1 flat offsets
+    int32_t* tile_first = nullptr;  // per pack tile: index of the first tensor that may intersect it
+};
+
+}  // namespace mc
+
+struct mc_layout {
+    int32_t n = 0;
+    int32_t k = 0;
+    int64_t N = 0;
+    std::vector<int64_t> off;         // n+1
+    std::vector<int64_t> bounds;      // k+1
+    std::vector<int32_t> tile_first;  // ceil(N / kPackTileElems) + 1
+    std::mutex mu;                    // guards dev[] during prepare / destroy
+    mc::DeviceTables dev[mc::kMaxDevices];
+};
+
+namespace mc {
+
+// Records a failed HIP call for mc_last_hip_error() and returns MC_ERR_HIP.
+int hip_fail(hipError_t e);
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Do the byte ranges [a, a+na) and [b, b+nb) intersect?  Empty ranges never do.
+inline bool overlaps(const void* a, uint64_t na, const void* b, uint64_t nb) {
+    if (na == 0 || nb == 0) return false;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+// Returns the device tables of L for the current device, uploading them on first use.
+int device_tables(mc_layout* L, const DeviceTables** out);
+
+int option(int which);
+
+}  // namespace mc
+
+#define MC_HIP_TRY(expr)                                  \
+    do {                                                  \
+        hipError_t mc_e_ = (expr);                        \
+        if (mc_e_ != hipSuccess) return mc::hip_fail(mc_e_); \
+    } while (0)

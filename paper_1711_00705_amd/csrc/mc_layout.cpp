@@ -1,0 +1,152 @@
+// Host side of the layout: flat offsets, colour bounds, pack-tile table, options, errors.
+// Nothing in this file touches the GPU.
+#include <atomic>
+#include <new>
+
+#include "mc_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+std::atomic<int> g_ru_unroll{2};
+std::atomic<int> g_ru_nontemporal{0};
+std::atomic<int> g_ru_block{256};
+
+}  // namespace
+
+namespace mc {
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = static_cast<int>(e);
+    return MC_ERR_HIP;
+}
+
+int option(int which) {
+    switch (which) {
+        case MC_OPT_RU_UNROLL: return g_ru_unroll.load(std::memory_order_relaxed);
+        case MC_OPT_RU_NONTEMPORAL: return g_ru_nontemporal.load(std::memory_order_relaxed);
+        case MC_OPT_RU_BLOCK: return g_ru_block.load(std::memory_order_relaxed);
+        default: return -1;
+    }
+}
+
+}  // namespace mc
+
+extern "C" {
+
+int mc_layout_create(const int64_t* numel, int32_t n_tensors, int32_t k_colours, mc_layout** out) {
+    if (out) *out = nullptr;
+    if (!numel || !out || n_tensors < 1 || k_colours < 1) return MC_ERR_INVALID_ARG;
+    constexpr int64_t kMaxTotal = int64_t(1) << 40;
+    int64_t total = 0;
+    for (int32_t t = 0; t < n_tensors; ++t) {
+        if (numel[t] < 0 || numel[t] > kMaxTotal) return MC_ERR_INVALID_ARG;
+        total += numel[t];
+        if (total > kMaxTotal) return MC_ERR_INVALID_ARG;
+    }
+    mc_layout* L = new (std::nothrow) mc_layout;
+    if (!L) return MC_ERR_ALLOC;
+    try {
+        L->n = n_tensors;
+        L->k = k_colours;
+        L->N = total;
+        L->off.resize(size_t(n_tensors) + 1);
+        L->off[0] = 0;
+        for (int32_t t = 0; t < n_tensors; ++t) L->off[t + 1] = L->off[t] + numel[t];
+
+        // Section 4.2: k contiguous chunks.  Equal length C (a multiple of 256 elements so that
+        // every colour starts on a 1 KiB boundary), the last non-empty one shorter.
+        const int64_t a = MC_COLOUR_ALIGN_ELEMS;
+        int64_t C = total / k_colours + (total % k_colours != 0);
+        C = (C + a - 1) / a * a;
+        L->bounds.resize(size_t(k_colours) + 1);
+        for (int32_t c = 0; c <= k_colours; ++c) {
+            const bool past_end = C == 0 || int64_t(c) >= (total + C - 1) / C;
+            L->bounds[c] = past_end ? total : int64_t(c) * C;
+        }
+
+        // For each pack tile, the first tensor whose range ends after the tile's first element.
+        const int64_t tiles = (total + mc::kPackTileElems - 1) / mc::kPackTileElems;
+        L->tile_first.resize(size_t(tiles) + 1);
+        int32_t t = 0;
+        for (int64_t j = 0; j <= tiles; ++j) {
+            const int64_t first = j * mc::kPackTileElems;
+            while (t < n_tensors && L->off[t + 1] <= first) ++t;
+            L->tile_first[j] = t;  // == n_tensors only when first >= N
+        }
+    } catch (const std::bad_alloc&) {
+        delete L;
+        return MC_ERR_ALLOC;
+    }
+    *out = L;
+    return MC_OK;
+}
+
+int mc_layout_total(const mc_layout* L, int64_t* N) {
+    if (!L || !N) return MC_ERR_INVALID_ARG;
+    *N = L->N;
+    return MC_OK;
+}
+
+int mc_layout_counts(const mc_layout* L, int32_t* n_tensors, int32_t* k_colours) {
+    if (!L || !n_tensors || !k_colours) return MC_ERR_INVALID_ARG;
+    *n_tensors = L->n;
+    *k_colours = L->k;
+    return MC_OK;
+}
+
+int mc_layout_tensor_offsets(const mc_layout* L, int64_t* off) {
+    if (!L || !off) return MC_ERR_INVALID_ARG;
+    for (size_t i = 0; i < L->off.size(); ++i) off[i] = L->off[i];
+    return MC_OK;
+}
+
+int mc_layout_colour_bounds(const mc_layout* L, int64_t* b) {
+    if (!L || !b) return MC_ERR_INVALID_ARG;
+    for (size_t i = 0; i < L->bounds.size(); ++i) b[i] = L->bounds[i];
+    return MC_OK;
+}
+
+const char* mc_strerror(int code) {
+    switch (code) {
+        case MC_OK: return "ok";
+        case MC_ERR_INVALID_ARG: return "invalid argument";
+        case MC_ERR_ALIGN: return "buffer is not sufficiently aligned";
+        case MC_ERR_OVERLAP: return "buffers overlap";
+        case MC_ERR_ALLOC: return "host allocation failed";
+        case MC_ERR_HIP: return "HIP runtime call failed";
+        default: return "unknown error code";
+    }
+}
+
+int mc_last_hip_error(void) { return g_last_hip_error; }
+
+int mc_set_option(int option, int value) {
+    switch (option) {
+        case MC_OPT_RU_UNROLL:
+            if (value != 1 && value != 2 && value != 4) return MC_ERR_INVALID_ARG;
+            g_ru_unroll.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_RU_NONTEMPORAL:
+            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
+            g_ru_nontemporal.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_RU_BLOCK:
+            if (value != 256 && value != 512) return MC_ERR_INVALID_ARG;
+            g_ru_block.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        default:
+            return MC_ERR_INVALID_ARG;
+    }
+}
+
+int mc_get_option(int option, int* value) {
+    if (!value) return MC_ERR_INVALID_ARG;
+    const int v = mc::option(option);
+    if (v < 0) return MC_ERR_INVALID_ARG;
+    *value = v;
+    return MC_OK;
+}
+
+}  // extern "C"

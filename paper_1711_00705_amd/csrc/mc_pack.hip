@@ -1,0 +1,197 @@
+// a2 / a5: gather per-layer tensors into the flat payload (pack) and scatter it back (unpack).
+//
+// The flat side is always walked in 16-byte vectors aligned to the payload, so flat traffic is
+// fully coalesced 128-bit accesses.  The tensor side is a 128-bit access when the four
+// elements lie in one tensor and its address happens to be 16-byte aligned too (always the
+// case for layouts whose tensor sizes are multiples of four elements and whose tensors are
+// 16-byte aligned, like the CNN payloads), and four 32-bit accesses otherwise.
+//
+// Device pointers of the tensors travel in the kernel-argument block (no staging copy, no
+// synchronisation); a layout with more tensors than fit is processed in several launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "mc_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kVecPerThread = int(mc::kPackTileElems / 4 / kThreads);  // 16-byte vectors per thread
+static_assert(mc::kPackTileElems == int64_t(kThreads) * 4 * kVecPerThread, "tile shape");
+
+struct PtrBatch {
+    void* p[mc::kPackMaxPtrs];
+};
+
+// One launch covers tensors [t0, t1), i.e. flat elements [off[t0], off[t1]), tile by tile.
+// UNPACK = false: tensors -> flat.  UNPACK = true: flat -> tensors.
+template <bool UNPACK>
+__global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
+    PtrBatch ptrs, const int64_t* __restrict__ off, const int32_t* __restrict__ tile_first,
+    uint32_t* flat, int64_t N, int32_t t0, int32_t t1, int64_t tile0) {
+    const int64_t tile = tile0 + blockIdx.x;
+    const int64_t lo = off[t0];
+    const int64_t hi = off[t1];
+    const int32_t t_tile = max(tile_first[tile], t0);
+    const int64_t tile_base = tile * mc::kPackTileElems;
+
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) {
+        const int64_t i = tile_base + (int64_t(j) * kThreads + threadIdx.x) * 4;
+        if (i >= hi || i + 4 <= lo) continue;
+        const int64_t first = i > lo ? i : lo;
+        int32_t t = t_tile;
+        while (off[t + 1] <= first) ++t;  // ends: first < hi == off[t1]
+
+        const bool one_tensor = i >= lo && i + 4 <= off[t + 1];
+        if (one_tensor) {
+            uint32_t* src = static_cast<uint32_t*>(ptrs.p[t - t0]) + (i - off[t]);
+            if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+                if (UNPACK)
+                    *reinterpret_cast<uint4*>(src) = *reinterpret_cast<const uint4*>(flat + i);
+                else
+                    *reinterpret_cast<uint4*>(flat + i) = *reinterpret_cast<const uint4*>(src);
+            } else if (UNPACK) {
+                const uint4 q = *reinterpret_cast<const uint4*>(flat + i);
+                src[0] = q.x;
+                src[1] = q.y;
+                src[2] = q.z;
+                src[3] = q.w;
+            } else {
+                uint4 q;
+                q.x = src[0];
+                q.y = src[1];
+                q.z = src[2];
+                q.w = src[3];
+                *reinterpret_cast<uint4*>(flat + i) = q;
+            }
+            continue;
+        }
+        // The vector straddles a tensor boundary, the launch's range or the payload's end.
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t idx = i + e;
+            if (idx < lo || idx >= hi) continue;
+            while (off[t + 1] <= idx) ++t;
+            uint32_t* elem = static_cast<uint32_t*>(ptrs.p[t - t0]) + (idx - off[t]);
+            if (UNPACK)
+                *elem = flat[idx];
+            else
+                flat[idx] = *elem;
+        }
+    }
+    (void)N;
+}
+
+template <bool UNPACK>
+int run(mc_layout* L, void* const* tensors, void* flat, void* stream) {
+    if (!L || !tensors) return MC_ERR_INVALID_ARG;
+    if (L->N == 0) return MC_OK;
+    if (!flat) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(flat, 16)) return MC_ERR_ALIGN;
+    const uint64_t flat_bytes = uint64_t(L->N) * 4;
+    for (int32_t t = 0; t < L->n; ++t) {
+        const int64_t cnt = L->off[t + 1] - L->off[t];
+        if (cnt == 0) continue;
+        if (!tensors[t]) return MC_ERR_INVALID_ARG;
+        if (!mc::aligned(tensors[t], 4)) return MC_ERR_ALIGN;
+        if (mc::overlaps(tensors[t], uint64_t(cnt) * 4, flat, flat_bytes)) return MC_ERR_OVERLAP;
+    }
+    const mc::DeviceTables* dt = nullptr;
+    const int rc = mc::device_tables(L, &dt);
+    if (rc != MC_OK) return rc;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int32_t t0 = 0; t0 < L->n; t0 += mc::kPackMaxPtrs) {
+        const int32_t t1 = std::min<int32_t>(L->n, t0 + mc::kPackMaxPtrs);
+        const int64_t lo = L->off[t0], hi = L->off[t1];
+        if (lo == hi) continue;
+        PtrBatch batch;
+        for (int32_t t = t0; t < t1; ++t) batch.p[t - t0] = tensors[t];
+        for (int32_t t = t1 - t0; t < mc::kPackMaxPtrs; ++t) batch.p[t] = nullptr;
+        const int64_t tile0 = lo / mc::kPackTileElems;
+        const int64_t tile_end = (hi + mc::kPackTileElems - 1) / mc::kPackTileElems;
+        hipLaunchKernelGGL(gather_scatter_kernel<UNPACK>, dim3(unsigned(tile_end - tile0)),
+                           dim3(kThreads), 0, s, batch, dt->off, dt->tile_first,
+                           static_cast<uint32_t*>(flat), L->N, t0, t1, tile0);
+        MC_HIP_TRY(hipGetLastError());
+    }
+    return MC_OK;
+}
+
+}  // namespace
+
+namespace mc {
+
+int device_tables(mc_layout* L, const DeviceTables** out) {
+    int dev = 0;
+    MC_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return MC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(L->mu);
+    DeviceTables& d = L->dev[dev];
+    if (!d.ready) {
+        int64_t* off = nullptr;
+        int32_t* tf = nullptr;
+        const size_t off_bytes = L->off.size() * sizeof(int64_t);
+        const size_t tf_bytes = L->tile_first.size() * sizeof(int32_t);
+        MC_HIP_TRY(hipMalloc(reinterpret_cast<void**>(&off), off_bytes));
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&tf), tf_bytes);
+        if (e == hipSuccess) e = hipMemcpy(off, L->off.data(), off_bytes, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(tf, L->tile_first.data(), tf_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(off);
+            (void)hipFree(tf);
+            return hip_fail(e);
+        }
+        d.off = off;
+        d.tile_first = tf;
+        d.ready = true;
+    }
+    *out = &d;
+    return MC_OK;
+}
+
+}  // namespace mc
+
+extern "C" {
+
+int mc_layout_prepare(mc_layout* L) {
+    if (!L) return MC_ERR_INVALID_ARG;
+    const mc::DeviceTables* dt = nullptr;
+    return mc::device_tables(L, &dt);
+}
+
+int mc_layout_destroy(mc_layout* L) {
+    if (!L) return MC_OK;
+    int rc = MC_OK;
+    {
+        std::lock_guard<std::mutex> lock(L->mu);
+        int cur = -1;
+        bool any = false;
+        for (int d = 0; d < mc::kMaxDevices; ++d) any = any || L->dev[d].ready;
+        if (any && hipGetDevice(&cur) != hipSuccess) cur = -1;
+        for (int d = 0; d < mc::kMaxDevices; ++d) {
+            mc::DeviceTables& t = L->dev[d];
+            if (!t.ready) continue;
+            hipError_t e = hipSetDevice(d);
+            if (e == hipSuccess) e = hipFree(t.off);
+            if (e == hipSuccess) e = hipFree(t.tile_first);
+            if (e != hipSuccess) rc = mc::hip_fail(e);
+            t.ready = false;
+        }
+        if (any && cur >= 0) (void)hipSetDevice(cur);
+    }
+    delete L;
+    return rc;
+}
+
+int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream) {
+    return run<false>(L, const_cast<void* const*>(tensors), flat, stream);
+}
+
+int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream) {
+    return run<true>(L, tensors, const_cast<void*>(flat), stream);
+}
+
+}  // extern "C"

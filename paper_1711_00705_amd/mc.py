@@ -1,0 +1,175 @@
+"""Thin ctypes binding of libmc.so: the same entry points as include/mc.h, argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; there is no
+fallback of any kind -- a missing or unloadable library raises at import of this module.
+
+Device buffers are passed as integer addresses (e.g. ``torch.Tensor.data_ptr()``), the
+stream as the integer ``hipStream_t`` (e.g. ``torch.cuda.current_stream().cuda_stream``).
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_ALIGN = -2
+ERR_OVERLAP = -3
+ERR_ALLOC = -4
+ERR_HIP = -5
+MAX_P = 32
+COLOUR_ALIGN_ELEMS = 256
+OPT_RU_UNROLL = 1
+OPT_RU_NONTEMPORAL = 2
+OPT_RU_BLOCK = 3
+
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_vpp = ctypes.POINTER(ctypes.c_void_p)
+_vp = ctypes.c_void_p
+
+# name -> (restype, argtypes): one entry per declaration in include/mc.h
+SIGNATURES = {
+    "mc_layout_create": (ctypes.c_int, [_i64p, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_vp)]),
+    "mc_layout_destroy": (ctypes.c_int, [_vp]),
+    "mc_layout_prepare": (ctypes.c_int, [_vp]),
+    "mc_layout_total": (ctypes.c_int, [_vp, _i64p]),
+    "mc_layout_counts": (ctypes.c_int, [_vp, _i32p, _i32p]),
+    "mc_layout_tensor_offsets": (ctypes.c_int, [_vp, _i64p]),
+    "mc_layout_colour_bounds": (ctypes.c_int, [_vp, _i64p]),
+    "mc_pack": (ctypes.c_int, [_vp, _vpp, _vp, _vp]),
+    "mc_unpack": (ctypes.c_int, [_vp, _vp, _vpp, _vp]),
+    "mc_reduce_update": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
+                                        ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "mc_last_hip_error": (ctypes.c_int, []),
+    "mc_set_option": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+    "mc_get_option": (ctypes.c_int, [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]),
+}
+
+
+def _load() -> ctypes.CDLL:
+    path = _build.library_path(build_if_missing=True)
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)          # AttributeError if the symbol is not exported
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+lib = _load()
+LIBRARY_PATH = lib._name
+
+
+class McError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib.mc_strerror(code).decode()
+        if code == ERR_HIP:
+            msg += " (hipError_t %d)" % lib.mc_last_hip_error()
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+def _check(code: int, where: str) -> None:
+    if code != OK:
+        raise McError(code, where)
+
+
+def _ptr_table(ptrs: Sequence[Optional[int]]):
+    tab = (ctypes.c_void_p * max(len(ptrs), 1))()
+    for i, p in enumerate(ptrs):
+        tab[i] = p
+    return tab
+
+
+class Layout:
+    """Owns one ``mc_layout*``."""
+
+    def __init__(self, numel: Sequence[int], k_colours: int):
+        arr = np.ascontiguousarray(numel, dtype=np.int64)
+        self._h = _vp()
+        _check(lib.mc_layout_create(arr.ctypes.data_as(_i64p), int(arr.shape[0]), int(k_colours),
+                                    ctypes.byref(self._h)), "mc_layout_create")
+        n = ctypes.c_int32()
+        k = ctypes.c_int32()
+        _check(lib.mc_layout_counts(self._h, ctypes.byref(n), ctypes.byref(k)), "mc_layout_counts")
+        self.n, self.k = n.value, k.value
+        total = ctypes.c_int64()
+        _check(lib.mc_layout_total(self._h, ctypes.byref(total)), "mc_layout_total")
+        self.N = total.value
+
+    @property
+    def handle(self):
+        return self._h
+
+    def tensor_offsets(self) -> np.ndarray:
+        off = np.empty(self.n + 1, dtype=np.int64)
+        _check(lib.mc_layout_tensor_offsets(self._h, off.ctypes.data_as(_i64p)), "mc_layout_tensor_offsets")
+        return off
+
+    def colour_bounds(self) -> np.ndarray:
+        b = np.empty(self.k + 1, dtype=np.int64)
+        _check(lib.mc_layout_colour_bounds(self._h, b.ctypes.data_as(_i64p)), "mc_layout_colour_bounds")
+        return b
+
+    def prepare(self) -> None:
+        _check(lib.mc_layout_prepare(self._h), "mc_layout_prepare")
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, _vp()
+            _check(lib.mc_layout_destroy(h), "mc_layout_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def layout_create(numel: Sequence[int], k_colours: int) -> Layout:
+    return Layout(numel, k_colours)
+
+
+def pack(layout: Layout, tensor_ptrs: Sequence[Optional[int]], flat_ptr: Optional[int], stream: int = 0) -> None:
+    if len(tensor_ptrs) != layout.n:
+        raise ValueError("need one pointer per tensor of the layout")
+    _check(lib.mc_pack(layout.handle, _ptr_table(tensor_ptrs), flat_ptr, stream or None), "mc_pack")
+
+
+def unpack(layout: Layout, flat_ptr: Optional[int], tensor_ptrs: Sequence[Optional[int]], stream: int = 0) -> None:
+    if len(tensor_ptrs) != layout.n:
+        raise ValueError("need one pointer per tensor of the layout")
+    _check(lib.mc_unpack(layout.handle, flat_ptr, _ptr_table(tensor_ptrs), stream or None), "mc_unpack")
+
+
+def reduce_update(layout: Layout, contrib_ptrs: Sequence[Optional[int]], order, grad_out_ptr: Optional[int],
+                  weights_ptr: Optional[int], momentum_ptr: Optional[int],
+                  lr: float, mu: float, wd: float, stream: int = 0) -> None:
+    P = len(contrib_ptrs)
+    optr = None
+    if order is not None:
+        o = np.ascontiguousarray(order, dtype=np.int32)
+        if o.size != layout.k * P:
+            raise ValueError("order must hold k_colours * P entries")
+        optr = o.ctypes.data_as(_i32p)
+    _check(lib.mc_reduce_update(layout.handle, _ptr_table(contrib_ptrs), P, optr, grad_out_ptr,
+                                weights_ptr, momentum_ptr, lr, mu, wd, stream or None), "mc_reduce_update")
+
+
+def set_option(option: int, value: int) -> None:
+    _check(lib.mc_set_option(option, value), "mc_set_option")
+
+
+def get_option(option: int) -> int:
+    v = ctypes.c_int()
+    _check(lib.mc_get_option(option, ctypes.byref(v)), "mc_get_option")
+    return v.value
+
+
+def strerror(code: int) -> str:
+    return lib.mc_strerror(code).decode()
