@@ -1,0 +1,310 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-rank multi-colour reduce + SGD update step on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic gradients that are
+already resident in HBM as per-layer tensors:
+    P x mc_pack (per-layer tensors -> flat colour-chunked payload)
+    1 x mc_reduce_update (per-colour fixed-order sum fused with the SGD update, writes g)
+    1 x mc_unpack (updated weights -> per-layer tensors)
+The layout (a1) is built once per model, like the framework's flattening of its parameters;
+its cost is reported separately as `layout_create_ms`.
+
+Prints ONE JSON line.  `value` is algorithmic bytes of the whole step / wall time of the
+step; `roofline` is for the dominant kernel (reduce_update), timed with events on the
+stream it is launched on, inside the timed region; `cpu_baseline` is the CPU oracle timed
+on this machine's host cores on the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import threading
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+METRIC = "effective HBM GB/s (% of MI355X peak) and ms per ResNet-50-shaped reduce+update"
+
+
+def measured_traffic(workload, P, k):
+    """HBM-side bytes per reduce_update launch from the rocprofv3 counter runs whose summary
+    is kept under profiles/ (None when there is none for this workload)."""
+    path = os.path.join(ROOT, "profiles", f"reduce_update_{workload}_P{P}_k{k}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="resnet50",
+                    choices=["tiny", "resnet50", "resnet50_heavy", "vgg16", "googlenet"])
+    ap.add_argument("--sets", type=int, default=0,
+                    help="rotating sets of contribution tensors (0 = pick so that no step re-reads a cached set)")
+    ap.add_argument("--order", default="rotation", choices=["identity", "rotation"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--kernel-only", action="store_true",
+                    help="time only mc_reduce_update launches (for profiler runs)")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref):
+    """The oracle as it stands: whole step (P packs, reduce+update, unpack) on host cores."""
+    import oracle
+    O = oracle.Layout(cfg.sizes, cfg.k)
+    N = O.N
+    step_bytes = (8 * cfg.P + 4 * (cfg.P + 5) + 8) * N
+    w = oracle.pack(O, w_layers_host)
+    v = np.zeros(N, np.float32)
+
+    def one_step(step):
+        xs = [oracle.pack(O, ts) for ts in host_sets[step % len(host_sets)]]
+        g = oracle.reduce_update(O, xs, w, v, cfg.lr, cfg.mu, cfg.wd, order=order)
+        layers = oracle.unpack(O, w)
+        return g, layers
+
+    t0 = time.perf_counter()
+    g, _ = one_step(0)
+    first = time.perf_counter() - t0
+    parity_ref.update(g=g, w=w.copy(), v=v.copy())
+    n = max(1, min(200, int(seconds / max(first, 1e-4))))
+    t0 = time.perf_counter()
+    for s in range(1, n + 1):
+        one_step(s)
+    dt = (time.perf_counter() - t0) / n
+
+    # colours are independent (and so are the P packs): one host thread per colour / pack
+    ncpu = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    nthr = max(1, min(cfg.k, ncpu))
+    w2 = oracle.pack(O, w_layers_host)
+    v2 = np.zeros(N, np.float32)
+    g2 = np.empty(N, np.float32)
+
+    def threaded_step(step):
+        tensors = host_sets[step % len(host_sets)]
+        xs = [None] * cfg.P
+
+        def do_pack(p):
+            xs[p] = oracle.pack(O, tensors[p])
+        th = [threading.Thread(target=do_pack, args=(p,)) for p in range(cfg.P)]
+        [t.start() for t in th]
+        [t.join() for t in th]
+        seq = order if order is not None else np.tile(np.arange(cfg.P, dtype=np.int32), (cfg.k, 1))
+        colours = list(range(cfg.k))
+
+        def do_colours(tid):
+            for c in colours[tid::nthr]:
+                oracle.reduce_update_colour(O, c, xs, g2, w2, v2, cfg.lr, cfg.mu, cfg.wd, seq=seq[c])
+        th = [threading.Thread(target=do_colours, args=(i,)) for i in range(nthr)]
+        [t.start() for t in th]
+        [t.join() for t in th]
+        oracle.unpack(O, w2)
+
+    threaded_step(0)
+    n2 = max(1, min(200, int(0.5 * seconds / max(dt, 1e-4))))
+    t0 = time.perf_counter()
+    for s in range(1, n2 + 1):
+        threaded_step(s)
+    dt2 = (time.perf_counter() - t0) / n2
+    return {
+        "value": round(step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "ms_per_step": round(dt * 1e3, 3),
+        "sample": f"{n} whole steps ({cfg.P} packs + reduce+update + unpack) of the full {cfg.name} "
+                  f"workload, N={N}, single thread",
+        "threaded": {"value": round(step_bytes / dt2 / 1e9, 3), "unit": "GB/s",
+                     "cores": max(nthr, min(cfg.P, ncpu)), "ms_per_step": round(dt2 * 1e3, 3),
+                     "sample": f"{n2} whole steps, one host thread per colour ({nthr}) / per pack ({cfg.P})"},
+        "host_cpus": ncpu,
+    }
+
+
+def main():
+    args = parse()
+    world = int(os.environ.get("WORLD_SIZE", "1"))
+    if args.gpus != 1 or world != 1:
+        print("bench.py: this build measures one GPU's share of the step on ONE GPU; "
+              "--gpus must be 1 (no collectives or multi-GPU paths are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1711_00705_amd import mc, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    cfg = wl.workload(args.workload)
+    N, P, k = cfg.total, cfg.P, cfg.k
+    order = None if args.order == "identity" else wl.rotation_order(k, P)
+    set_bytes = 4 * N * P
+    # enough rotating sets that a step never finds its contributions in the 256 MB last-level cache
+    n_sets = args.sets or (cfg.steps if cfg.steps > 1 else max(3, int(np.ceil(1.2e9 / set_bytes))))
+    n_sets = min(n_sets, 100)
+
+    t0 = time.perf_counter()
+    L = mc.Layout(cfg.sizes, k)
+    layout_ms = (time.perf_counter() - t0) * 1e3
+    L.prepare()
+    stream = torch.cuda.current_stream()
+    sh = int(stream.cuda_stream)
+
+    def upload(layers):
+        return [torch.from_numpy(t).cuda() for t in layers]
+
+    # ---- inputs: seeded, host-generated, uploaded as separate per-layer tensors ------------
+    host_sets = []            # kept for the CPU baseline (first 3 sets only)
+    dev_sets, tables = [], []
+    for s in range(n_sets):
+        per_p = [wl.contribution_tensors(cfg.sizes, p, step=s, heavy_tail=cfg.heavy_tail) for p in range(P)]
+        if s < 3:
+            host_sets.append(per_p)
+        dev = [upload(ts) for ts in per_p]
+        dev_sets.append(dev)
+        tables.append([mc.ptr_table([t.data_ptr() for t in d]) for d in dev])
+    w_layers_host = wl.weight_tensors(cfg.sizes)
+    w_layers = upload(w_layers_host)
+    w_table = mc.ptr_table([t.data_ptr() for t in w_layers])
+    flats = [torch.empty(N, dtype=torch.float32, device="cuda") for _ in range(P)]
+    flat_table = mc.ptr_table([f.data_ptr() for f in flats])
+    w = torch.empty(N, dtype=torch.float32, device="cuda")
+    v = torch.zeros(N, dtype=torch.float32, device="cuda")
+    g = torch.empty(N, dtype=torch.float32, device="cuda")
+    mc.pack(L, w_table, w.data_ptr(), sh)
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        tabs = tables[i % n_sets]
+        for p in range(P):
+            mc.pack(L, tabs[p], flats[p].data_ptr(), sh)
+        if ev is not None:
+            ev[0].record(stream)
+        mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                         cfg.lr, cfg.mu, cfg.wd, sh)
+        if ev is not None:
+            ev[1].record(stream)
+        mc.unpack(L, w.data_ptr(), w_table, sh)
+
+    # ---- parity of the very first step against the oracle (same host bytes) ----------------
+    parity_ref, cpu = {}, None
+    step(0)
+    torch.cuda.synchronize()
+    first = dict(g=g.cpu().numpy(), w=w.cpu().numpy(), v=v.cpu().numpy())
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, order, host_sets, w_layers_host, args.cpu_seconds, parity_ref)
+        for key in ("g", "w", "v"):
+            a = first[key].view(np.uint32)
+            b = parity_ref[key].view(np.uint32)
+            if not np.array_equal(a, b):
+                print(f"bench.py: PARITY FAILURE on {key}: {int((a != b).sum())} words differ", file=sys.stderr)
+                sys.exit(4)
+    host_sets = None
+
+    if args.kernel_only:
+        for i in range(args.warmup):
+            mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                             cfg.lr, cfg.mu, cfg.wd, sh)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                             cfg.lr, cfg.mu, cfg.wd, sh)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        # known-size traffic for counter calibration: copy_kernel moves copy_bytes each way
+        copy_bytes = (N // 4) * 16
+        for i in range(3):
+            mc.copy(flats[0].data_ptr(), flats[1 % P].data_ptr() if P > 1 else g.data_ptr(), copy_bytes, sh)
+        torch.cuda.synchronize()
+        print(json.dumps({"kernel_only_ms": ms, "GBps": 4 * (P + 5) * N / ms / 1e6,
+                          "reduce_update_bytes": 4 * (P + 5) * N, "copy_bytes_each_way": copy_bytes}))
+        return
+
+    # ---- warm-up, then EXACTLY K timed steps ------------------------------------------------
+    for i in range(args.warmup):
+        step(i + 1)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + 1 + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    ru_ms = np.array([a.elapsed_time(b) for a, b in events])
+
+    # ---- the pieces on their own (events around back-to-back launches), and the copy yardstick
+    def timed(fn, reps):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        fn(0)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for r in range(reps):
+            fn(r + 1)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    reps = max(10, min(args.steps, 50))
+    pack_ms = timed(lambda r: mc.pack(L, tables[r % n_sets][r % P], flats[r % P].data_ptr(), sh), reps)
+    unpack_ms = timed(lambda r: mc.unpack(L, w.data_ptr(), w_table, sh), reps)
+    copy_ms = timed(lambda r: mc.copy(flats[r % P].data_ptr(), flats[(r + 1) % P].data_ptr(), 4 * (N // 4) * 4, sh), reps)
+
+    step_bytes = (8 * P + 4 * (P + 5) + 8) * N
+    ru_bytes = 4 * (P + 5) * N
+    ru_avg = float(ru_ms.mean())
+    achieved = ru_bytes / ru_avg / 1e6
+    out = {
+        "metric": METRIC,
+        "value": round(step_bytes / ms_per_step / 1e6, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_tensors} tensors, N={N} fp32, P={P}, k={k}, "
+                               f"lr={cfg.lr} mu={cfg.mu} wd={cfg.wd}, order={args.order}, "
+                               f"{n_sets} rotating contribution sets",
+                   "step": f"{P} x mc_pack + mc_reduce_update (writes grad_out) + mc_unpack(weights)",
+                   "step_bytes": step_bytes},
+        "pct_of_hbm_peak": round(100 * step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
+        "reduce_update": {"ms": round(ru_avg, 4), "ms_min": round(float(ru_ms.min()), 4),
+                          "ms_median": round(float(np.median(ru_ms)), 4),
+                          "GBps": round(achieved, 1),
+                          "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2)},
+        "pack": {"ms": round(pack_ms, 4), "GBps": round(8 * N / pack_ms / 1e6, 1)},
+        "unpack": {"ms": round(unpack_ms, 4), "GBps": round(8 * N / unpack_ms / 1e6, 1)},
+        "copy_yardstick": {"ms": round(copy_ms, 4), "GBps": round(8 * (N // 4) * 4 / copy_ms / 1e6, 1)},
+        "layout_create_ms": round(layout_ms, 3),
+        "roofline": {"bound": "hbm", "kernel": "reduce_update_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(cfg.name, P, k), "bytes_per_launch": ru_bytes},
+        "cpu_baseline": cpu,
+        "parity_checked_first_step": cpu is not None,
+        "library": os.path.relpath(mc.LIBRARY_PATH, ROOT),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

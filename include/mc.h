@@ -123,15 +123,25 @@ int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P,
                      float lr, float mu, float wd, void* stream);
 
 /* ---- diagnostics and tuning ---------------------------------------------------------- */
+/* Plain device-to-device copy of n_bytes (a multiple of 16; dst and src device, 16-byte
+ * aligned, not overlapping) with the library's own 128-bit streaming kernel.  Not part of the
+ * method: it is the yardstick for achievable HBM bandwidth and the known-size traffic that
+ * hardware counters are calibrated against.  Errors: MC_ERR_INVALID_ARG, MC_ERR_ALIGN,
+ * MC_ERR_OVERLAP, MC_ERR_HIP. */
+int mc_copy(void* dst, const void* src, int64_t n_bytes, void* stream);
+
 const char* mc_strerror(int code);     /* static string, never NULL */
 int mc_last_hip_error(void);           /* raw hipError_t of this thread's last MC_ERR_HIP */
 
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  * Returns MC_ERR_INVALID_ARG for an unknown option or a value outside its range. */
 enum {
-    MC_OPT_RU_UNROLL = 1,       /* 16-byte vectors per thread per tile in reduce_update: 1, 2 or 4 */
-    MC_OPT_RU_NONTEMPORAL = 2,  /* 1: streaming (non-temporal) loads of contributions and store of grad_out */
-    MC_OPT_RU_BLOCK = 3         /* threads per workgroup in reduce_update: 256 or 512 */
+    MC_OPT_RU_UNROLL = 1,          /* 16-byte vectors per thread per tile in reduce_update: 1 or 2 */
+    MC_OPT_RU_NONTEMPORAL = 2,     /* bit 0: streaming (non-temporal) loads of the contributions;
+                                      bit 1: streaming store of grad_out.  Weights and momentum
+                                      always use the normal policy so that they stay cached. */
+    MC_OPT_PACK_NONTEMPORAL = 3    /* pack/unpack: bit 0 streaming access to the per-layer
+                                      tensors, bit 1 streaming access to the flat payload */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

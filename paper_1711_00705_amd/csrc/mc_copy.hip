@@ -1,0 +1,46 @@
+// A plain 128-bit device-to-device copy: the yardstick the other kernels are measured
+// against (achievable HBM bandwidth) and the known-size traffic used to calibrate hardware
+// counters.  One 16-byte vector per thread per step, four steps per thread.
+#include <hip/hip_runtime.h>
+
+#include "mc_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kVecPerThread = 4;
+
+__global__ __launch_bounds__(kThreads) void copy_kernel(uint4* __restrict__ dst,
+                                                        const uint4* __restrict__ src, int64_t n_vec) {
+    const int64_t base = int64_t(blockIdx.x) * (kThreads * kVecPerThread) + threadIdx.x;
+    uint4 r[kVecPerThread];
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) {
+        const int64_t i = base + int64_t(j) * kThreads;
+        if (i < n_vec) r[j] = src[i];
+    }
+#pragma unroll
+    for (int j = 0; j < kVecPerThread; ++j) {
+        const int64_t i = base + int64_t(j) * kThreads;
+        if (i < n_vec) dst[i] = r[j];
+    }
+}
+
+}  // namespace
+
+extern "C" int mc_copy(void* dst, const void* src, int64_t n_bytes, void* stream) {
+    if (n_bytes < 0 || (n_bytes & 15) != 0) return MC_ERR_INVALID_ARG;
+    if (n_bytes == 0) return MC_OK;
+    if (!dst || !src) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(dst, 16) || !mc::aligned(src, 16)) return MC_ERR_ALIGN;
+    if (mc::overlaps(dst, uint64_t(n_bytes), src, uint64_t(n_bytes))) return MC_ERR_OVERLAP;
+    const int64_t n_vec = n_bytes / 16;
+    const int64_t per_block = int64_t(kThreads) * kVecPerThread;
+    const int64_t blocks = (n_vec + per_block - 1) / per_block;
+    if (blocks > 0x7fffffff) return MC_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(copy_kernel, dim3(unsigned(blocks)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src), n_vec);
+    MC_HIP_TRY(hipGetLastError());
+    return MC_OK;
+}

@@ -10,8 +10,8 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 std::atomic<int> g_ru_unroll{2};
-std::atomic<int> g_ru_nontemporal{0};
-std::atomic<int> g_ru_block{256};
+std::atomic<int> g_ru_nontemporal{3};
+std::atomic<int> g_pack_nontemporal{0};
 
 }  // namespace
 
@@ -26,7 +26,7 @@ int option(int which) {
     switch (which) {
         case MC_OPT_RU_UNROLL: return g_ru_unroll.load(std::memory_order_relaxed);
         case MC_OPT_RU_NONTEMPORAL: return g_ru_nontemporal.load(std::memory_order_relaxed);
-        case MC_OPT_RU_BLOCK: return g_ru_block.load(std::memory_order_relaxed);
+        case MC_OPT_PACK_NONTEMPORAL: return g_pack_nontemporal.load(std::memory_order_relaxed);
         default: return -1;
     }
 }
@@ -125,16 +125,16 @@ int mc_last_hip_error(void) { return g_last_hip_error; }
 int mc_set_option(int option, int value) {
     switch (option) {
         case MC_OPT_RU_UNROLL:
-            if (value != 1 && value != 2 && value != 4) return MC_ERR_INVALID_ARG;
+            if (value != 1 && value != 2) return MC_ERR_INVALID_ARG;
             g_ru_unroll.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_RU_NONTEMPORAL:
-            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
+            if (value < 0 || value > 3) return MC_ERR_INVALID_ARG;
             g_ru_nontemporal.store(value, std::memory_order_relaxed);
             return MC_OK;
-        case MC_OPT_RU_BLOCK:
-            if (value != 256 && value != 512) return MC_ERR_INVALID_ARG;
-            g_ru_block.store(value, std::memory_order_relaxed);
+        case MC_OPT_PACK_NONTEMPORAL:
+            if (value < 0 || value > 3) return MC_ERR_INVALID_ARG;
+            g_pack_nontemporal.store(value, std::memory_order_relaxed);
             return MC_OK;
         default:
             return MC_ERR_INVALID_ARG;

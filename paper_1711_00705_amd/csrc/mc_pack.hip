@@ -24,12 +24,38 @@ struct PtrBatch {
     void* p[mc::kPackMaxPtrs];
 };
 
+template <bool NT>
+__device__ __forceinline__ uint4 ld4(const uint32_t* p) {
+    if (NT) {
+        uint4 r;
+        r.x = __builtin_nontemporal_load(p + 0);
+        r.y = __builtin_nontemporal_load(p + 1);
+        r.z = __builtin_nontemporal_load(p + 2);
+        r.w = __builtin_nontemporal_load(p + 3);
+        return r;
+    }
+    return *reinterpret_cast<const uint4*>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
+    if (NT) {
+        __builtin_nontemporal_store(q.x, p + 0);
+        __builtin_nontemporal_store(q.y, p + 1);
+        __builtin_nontemporal_store(q.z, p + 2);
+        __builtin_nontemporal_store(q.w, p + 3);
+    } else {
+        *reinterpret_cast<uint4*>(p) = q;
+    }
+}
+
 // One launch covers tensors [t0, t1), i.e. flat elements [off[t0], off[t1]), tile by tile.
 // UNPACK = false: tensors -> flat.  UNPACK = true: flat -> tensors.
-template <bool UNPACK>
+// NT_T / NT_F: streaming (non-temporal) policy for the tensor side / the flat side.
+template <bool UNPACK, bool NT_T, bool NT_F>
 __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
     PtrBatch ptrs, const int64_t* __restrict__ off, const int32_t* __restrict__ tile_first,
-    uint32_t* flat, int64_t N, int32_t t0, int32_t t1, int64_t tile0) {
+    uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0) {
     const int64_t tile = tile0 + blockIdx.x;
     const int64_t lo = off[t0];
     const int64_t hi = off[t1];
@@ -49,11 +75,11 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
             uint32_t* src = static_cast<uint32_t*>(ptrs.p[t - t0]) + (i - off[t]);
             if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
                 if (UNPACK)
-                    *reinterpret_cast<uint4*>(src) = *reinterpret_cast<const uint4*>(flat + i);
+                    st4<NT_T>(src, ld4<NT_F>(flat + i));
                 else
-                    *reinterpret_cast<uint4*>(flat + i) = *reinterpret_cast<const uint4*>(src);
+                    st4<NT_F>(flat + i, ld4<NT_T>(src));
             } else if (UNPACK) {
-                const uint4 q = *reinterpret_cast<const uint4*>(flat + i);
+                const uint4 q = ld4<NT_F>(flat + i);
                 src[0] = q.x;
                 src[1] = q.y;
                 src[2] = q.z;
@@ -64,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
                 q.y = src[1];
                 q.z = src[2];
                 q.w = src[3];
-                *reinterpret_cast<uint4*>(flat + i) = q;
+                st4<NT_F>(flat + i, q);
             }
             continue;
         }
@@ -81,7 +107,6 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
                 flat[idx] = *elem;
         }
     }
-    (void)N;
 }
 
 template <bool UNPACK>
@@ -103,6 +128,7 @@ int run(mc_layout* L, void* const* tensors, void* flat, void* stream) {
     if (rc != MC_OK) return rc;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const int nt = mc::option(MC_OPT_PACK_NONTEMPORAL);
     for (int32_t t0 = 0; t0 < L->n; t0 += mc::kPackMaxPtrs) {
         const int32_t t1 = std::min<int32_t>(L->n, t0 + mc::kPackMaxPtrs);
         const int64_t lo = L->off[t0], hi = L->off[t1];
@@ -112,9 +138,14 @@ int run(mc_layout* L, void* const* tensors, void* flat, void* stream) {
         for (int32_t t = t1 - t0; t < mc::kPackMaxPtrs; ++t) batch.p[t] = nullptr;
         const int64_t tile0 = lo / mc::kPackTileElems;
         const int64_t tile_end = (hi + mc::kPackTileElems - 1) / mc::kPackTileElems;
-        hipLaunchKernelGGL(gather_scatter_kernel<UNPACK>, dim3(unsigned(tile_end - tile0)),
-                           dim3(kThreads), 0, s, batch, dt->off, dt->tile_first,
-                           static_cast<uint32_t*>(flat), L->N, t0, t1, tile0);
+        const dim3 grid(unsigned(tile_end - tile0)), block(kThreads);
+        uint32_t* f = static_cast<uint32_t*>(flat);
+        switch (nt & 3) {
+            case 0: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, false, false>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
+            case 1: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, true, false>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
+            case 2: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, false, true>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
+            default: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, true, true>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
+        }
         MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;

@@ -20,6 +20,7 @@
 
 namespace {
 
+constexpr int kThreads = 256;  // workgroup size
 constexpr int kMaxSegs = 32;     // colours per launch
 constexpr int kPtrSlots = 256;   // permuted contribution pointers per launch (kMaxSegs*P <= this)
 
@@ -181,50 +182,37 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
     }
 }
 
-template <int P, int U, int THREADS, bool HAS_G>
+template <int P, int U, bool HAS_G>
 void launch_nt(int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    if (nt)
-        hipLaunchKernelGGL((reduce_update_kernel<P, U, THREADS, HAS_G, true, true>), dim3(blocks), dim3(THREADS), 0, s, a, Prt);
-    else
-        hipLaunchKernelGGL((reduce_update_kernel<P, U, THREADS, HAS_G, false, false>), dim3(blocks), dim3(THREADS), 0, s, a, Prt);
-}
-
-template <int P, int U, int THREADS>
-void launch_g(int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    if (a.g)
-        launch_nt<P, U, THREADS, true>(nt, blocks, s, a, Prt);
-    else
-        launch_nt<P, U, THREADS, false>(nt, blocks, s, a, Prt);
-}
-
-template <int P, int U>
-void launch_threads(int threads, int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    switch (threads) {
-        case 512: launch_g<P, U, 512>(nt, blocks, s, a, Prt); break;
-        default: launch_g<P, U, 256>(nt, blocks, s, a, Prt); break;
+    constexpr int T = kThreads;
+    switch (nt & 3) {
+        case 0: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, false, false>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
+        case 1: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, true, false>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
+        case 2: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, false, true>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
+        default: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, true, true>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
     }
 }
 
 template <int P>
-void launch_unroll(int unroll, int threads, int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    switch (unroll) {
-        case 1: launch_threads<P, 1>(threads, nt, blocks, s, a, Prt); break;
-        case 4: launch_threads<P, 4>(threads, nt, blocks, s, a, Prt); break;
-        default: launch_threads<P, 2>(threads, nt, blocks, s, a, Prt); break;
+void launch_unroll(int unroll, int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
+    if (unroll == 1) {
+        if (a.g) launch_nt<P, 1, true>(nt, blocks, s, a, Prt); else launch_nt<P, 1, false>(nt, blocks, s, a, Prt);
+    } else {
+        if (a.g) launch_nt<P, 2, true>(nt, blocks, s, a, Prt); else launch_nt<P, 2, false>(nt, blocks, s, a, Prt);
     }
 }
 
-void launch(int P, int unroll, int threads, int nt, unsigned blocks, hipStream_t s, const RuArgs& a) {
+void launch(int P, int unroll, int nt, unsigned blocks, hipStream_t s, const RuArgs& a) {
     switch (P) {
-        case 1: launch_unroll<1>(unroll, threads, nt, blocks, s, a, P); break;
-        case 2: launch_unroll<2>(unroll, threads, nt, blocks, s, a, P); break;
-        case 3: launch_unroll<3>(unroll, threads, nt, blocks, s, a, P); break;
-        case 4: launch_unroll<4>(unroll, threads, nt, blocks, s, a, P); break;
-        case 5: launch_unroll<5>(unroll, threads, nt, blocks, s, a, P); break;
-        case 6: launch_unroll<6>(unroll, threads, nt, blocks, s, a, P); break;
-        case 7: launch_unroll<7>(unroll, threads, nt, blocks, s, a, P); break;
-        case 8: launch_unroll<8>(unroll, threads, nt, blocks, s, a, P); break;
-        default: launch_unroll<0>(unroll, threads, nt, blocks, s, a, P); break;
+        case 1: launch_unroll<1>(unroll, nt, blocks, s, a, P); break;
+        case 2: launch_unroll<2>(unroll, nt, blocks, s, a, P); break;
+        case 3: launch_unroll<3>(unroll, nt, blocks, s, a, P); break;
+        case 4: launch_unroll<4>(unroll, nt, blocks, s, a, P); break;
+        case 5: launch_unroll<5>(unroll, nt, blocks, s, a, P); break;
+        case 6: launch_unroll<6>(unroll, nt, blocks, s, a, P); break;
+        case 7: launch_unroll<7>(unroll, nt, blocks, s, a, P); break;
+        case 8: launch_unroll<8>(unroll, nt, blocks, s, a, P); break;
+        default: launch_unroll<0>(unroll, nt, blocks, s, a, P); break;
     }
 }
 
@@ -264,7 +252,7 @@ extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, 
             if (mc::overlaps(bufs[i], bytes, bufs[j], bytes)) return MC_ERR_OVERLAP;
 
     const int unroll = mc::option(MC_OPT_RU_UNROLL);
-    const int threads = mc::option(MC_OPT_RU_BLOCK);
+    const int threads = kThreads;
     const int nt = mc::option(MC_OPT_RU_NONTEMPORAL);
     const int64_t tile = int64_t(threads) * 4 * unroll;
     const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / P);
@@ -311,7 +299,7 @@ extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, 
             a.first_block[i] = a.first_block[ns];
         }
         a.n_segs = ns;
-        launch(P, unroll, threads, nt, unsigned(blocks), s, a);
+        launch(P, unroll, nt, unsigned(blocks), s, a);
         MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;

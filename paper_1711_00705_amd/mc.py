@@ -24,7 +24,7 @@ MAX_P = 32
 COLOUR_ALIGN_ELEMS = 256
 OPT_RU_UNROLL = 1
 OPT_RU_NONTEMPORAL = 2
-OPT_RU_BLOCK = 3
+OPT_PACK_NONTEMPORAL = 3
 
 _i64p = ctypes.POINTER(ctypes.c_int64)
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -44,6 +44,7 @@ SIGNATURES = {
     "mc_unpack": (ctypes.c_int, [_vp, _vp, _vpp, _vp]),
     "mc_reduce_update": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
                                         ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_int64, _vp]),
     "mc_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "mc_last_hip_error": (ctypes.c_int, []),
     "mc_set_option": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
@@ -79,11 +80,21 @@ def _check(code: int, where: str) -> None:
         raise McError(code, where)
 
 
-def _ptr_table(ptrs: Sequence[Optional[int]]):
+def ptr_table(ptrs: Sequence[Optional[int]]):
+    """A host array of device addresses, reusable across calls (saves rebuilding it)."""
     tab = (ctypes.c_void_p * max(len(ptrs), 1))()
     for i, p in enumerate(ptrs):
         tab[i] = p
+    tab.count = len(ptrs)
     return tab
+
+
+def _ptr_table(ptrs):
+    return ptrs if isinstance(ptrs, ctypes.Array) else ptr_table(ptrs)
+
+
+def _count(ptrs) -> int:
+    return ptrs.count if isinstance(ptrs, ctypes.Array) else len(ptrs)
 
 
 class Layout:
@@ -136,13 +147,13 @@ def layout_create(numel: Sequence[int], k_colours: int) -> Layout:
 
 
 def pack(layout: Layout, tensor_ptrs: Sequence[Optional[int]], flat_ptr: Optional[int], stream: int = 0) -> None:
-    if len(tensor_ptrs) != layout.n:
+    if _count(tensor_ptrs) != layout.n:
         raise ValueError("need one pointer per tensor of the layout")
     _check(lib.mc_pack(layout.handle, _ptr_table(tensor_ptrs), flat_ptr, stream or None), "mc_pack")
 
 
 def unpack(layout: Layout, flat_ptr: Optional[int], tensor_ptrs: Sequence[Optional[int]], stream: int = 0) -> None:
-    if len(tensor_ptrs) != layout.n:
+    if _count(tensor_ptrs) != layout.n:
         raise ValueError("need one pointer per tensor of the layout")
     _check(lib.mc_unpack(layout.handle, flat_ptr, _ptr_table(tensor_ptrs), stream or None), "mc_unpack")
 
@@ -150,7 +161,7 @@ def unpack(layout: Layout, flat_ptr: Optional[int], tensor_ptrs: Sequence[Option
 def reduce_update(layout: Layout, contrib_ptrs: Sequence[Optional[int]], order, grad_out_ptr: Optional[int],
                   weights_ptr: Optional[int], momentum_ptr: Optional[int],
                   lr: float, mu: float, wd: float, stream: int = 0) -> None:
-    P = len(contrib_ptrs)
+    P = _count(contrib_ptrs)
     optr = None
     if order is not None:
         o = np.ascontiguousarray(order, dtype=np.int32)
@@ -159,6 +170,10 @@ def reduce_update(layout: Layout, contrib_ptrs: Sequence[Optional[int]], order, 
         optr = o.ctypes.data_as(_i32p)
     _check(lib.mc_reduce_update(layout.handle, _ptr_table(contrib_ptrs), P, optr, grad_out_ptr,
                                 weights_ptr, momentum_ptr, lr, mu, wd, stream or None), "mc_reduce_update")
+
+
+def copy(dst_ptr: Optional[int], src_ptr: Optional[int], n_bytes: int, stream: int = 0) -> None:
+    _check(lib.mc_copy(dst_ptr, src_ptr, n_bytes, stream or None), "mc_copy")
 
 
 def set_option(option: int, value: int) -> None:

@@ -22,7 +22,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
-    assert len(names) >= 14
+    assert len(names) >= 15
     raw = ctypes.CDLL(mc.LIBRARY_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in mc.h but not exported"
@@ -153,10 +153,10 @@ def test_empty_payload_is_a_no_op():
 
 
 def test_options():
-    assert mc.get_option(mc.OPT_RU_UNROLL) in (1, 2, 4)
-    for opt, good, bad in ((mc.OPT_RU_UNROLL, (1, 2, 4), (0, 3, 8)),
-                           (mc.OPT_RU_NONTEMPORAL, (0, 1), (-1, 2)),
-                           (mc.OPT_RU_BLOCK, (256, 512), (64, 1024))):
+    assert mc.get_option(mc.OPT_RU_UNROLL) in (1, 2)
+    for opt, good, bad in ((mc.OPT_RU_UNROLL, (1, 2), (0, 3, 4)),
+                           (mc.OPT_RU_NONTEMPORAL, (0, 1, 2, 3), (-1, 4)),
+                           (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4))):
         keep = mc.get_option(opt)
         for g in good:
             mc.set_option(opt, g)
@@ -166,3 +166,14 @@ def test_options():
         mc.set_option(opt, keep)
     assert _code(mc.set_option, 99, 0) == mc.ERR_INVALID_ARG
     assert _code(mc.get_option, 99) == mc.ERR_INVALID_ARG
+
+
+def test_copy_rejects_before_launch():
+    B = 0x10000000
+    assert _code(mc.copy, B, B + 4096, 0) == mc.OK                      # nothing to do
+    assert _code(mc.copy, B, B + 4096, 100) == mc.ERR_INVALID_ARG       # not a multiple of 16
+    assert _code(mc.copy, B, B + 4096, -16) == mc.ERR_INVALID_ARG
+    assert _code(mc.copy, None, B, 1024) == mc.ERR_INVALID_ARG
+    assert _code(mc.copy, B, None, 1024) == mc.ERR_INVALID_ARG
+    assert _code(mc.copy, B + 8, B + 4096, 1024) == mc.ERR_ALIGN
+    assert _code(mc.copy, B, B + 512, 1024) == mc.ERR_OVERLAP

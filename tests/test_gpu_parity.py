@@ -17,7 +17,7 @@ import gpu_harness as gh  # noqa: E402
 
 @pytest.fixture(autouse=True)
 def _restore_options():
-    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL, mc.OPT_RU_BLOCK)}
+    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL, mc.OPT_PACK_NONTEMPORAL)}
     yield
     for o, v in keep.items():
         mc.set_option(o, v)
@@ -51,19 +51,19 @@ def test_tiny_config(order_kind, misalign):
     st.check(gpu, ref, cfg.lr, cfg.mu, cfg.wd, "tiny")
 
 
-@pytest.mark.parametrize("unroll", [1, 2, 4])
-@pytest.mark.parametrize("block", [256, 512])
-@pytest.mark.parametrize("nt", [0, 1])
-def test_launch_shapes_do_not_change_bits(unroll, block, nt):
+@pytest.mark.parametrize("unroll", [1, 2])
+@pytest.mark.parametrize("nt", [0, 1, 2, 3])
+@pytest.mark.parametrize("pack_nt", [0, 1, 2, 3])
+def test_launch_shapes_do_not_change_bits(unroll, nt, pack_nt):
     mc.set_option(mc.OPT_RU_UNROLL, unroll)
-    mc.set_option(mc.OPT_RU_BLOCK, block)
+    mc.set_option(mc.OPT_PACK_NONTEMPORAL, pack_nt)
     mc.set_option(mc.OPT_RU_NONTEMPORAL, nt)
     sizes = [30000, 1, 4097, 12345, 70001]      # several tiles of every shape + ragged tail
     st = gh.Step(sizes, 3)
     xs, w, v = _inputs(sizes, 5, v_zero=False)
-    print(f"shapes unroll={unroll} block={block} nt={nt}", flush=True)
-    gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=wl.rotation_order(3, 5))
-    st.check(gpu, ref, 0.1, 0.9, 1e-4, f"unroll={unroll} block={block} nt={nt}")
+    print(f"shapes unroll={unroll} nt={nt} pack_nt={pack_nt}", flush=True)
+    gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=wl.rotation_order(3, 5), misalign=[0, 1, 0, 3])
+    st.check(gpu, ref, 0.1, 0.9, 1e-4, f"unroll={unroll} nt={nt} pack_nt={pack_nt}")
 
 
 @pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 6, 7, 8, 9, 16, 32])
@@ -309,3 +309,15 @@ def test_non_default_stream():
     with torch.cuda.stream(side):
         gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4)
     st.check(gpu, ref, 0.1, 0.9, 1e-4, "side stream")
+
+
+def test_copy_yardstick_copies():
+    n = 1_000_003 * 4
+    src = torch.arange(n, dtype=torch.int32, device="cuda").view(torch.float32)
+    buf = gh.dev_empty(n + 128)
+    dst = buf[64:64 + n]
+    mc.copy(dst.data_ptr(), src.data_ptr(), 4 * n, gh.stream_handle())
+    torch.cuda.synchronize()
+    h = buf.cpu().numpy().view(np.uint32)
+    assert np.all(h[:64] == 0xFFFFFFFF) and np.all(h[64 + n:] == 0xFFFFFFFF)
+    assert np.array_equal(h[64:64 + n], np.arange(n, dtype=np.uint32))
