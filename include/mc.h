@@ -122,6 +122,46 @@ int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P,
                      const int32_t* order, void* grad_out, void* weights, void* momentum,
                      float lr, float mu, float wd, void* stream);
 
+/* ---- roles: the multi-colour trees and per-colour term counts -------------------------
+ * Section 4.2: for each of the k colours the nodes are arranged in a k-ary breadth-first
+ * spanning tree; the non-leaf nodes (root included) of different colours are disjoint; roots
+ * and non-leaf nodes sum, leaves only send; the result is broadcast from the k roots.  The
+ * paper's example (Figure 2): 8 nodes, 4 colours -> colour 0 rooted at node 0 with node 1 its
+ * only other non-leaf, colour 1 rooted at node 2 with node 3.
+ *
+ * Node placement (the paper leaves it open): a tree needs s = ceil((n_nodes-1)/k) non-leaf
+ * nodes; colour c fills a complete k-ary tree breadth first with the node sequence
+ * c*s, c*s+1, ... (mod n_nodes).  Disjoint non-leaf sets exist iff k*s <= n_nodes; otherwise
+ * both functions return MC_ERR_INVALID_ARG.  Host-only.
+ *
+ * mc_colour_trees: parent (host, k_colours*n_nodes int32): parent[c*n_nodes + r] is the parent
+ *   of node r in colour c's tree, -1 for the root.
+ * mc_rank_roles: for one rank, per colour c: role[c] (MC_ROLE_*), n_children[c], and
+ *   children[c*k_colours + j] = j-th child (in arrival order), -1 beyond n_children[c]. */
+enum { MC_ROLE_LEAF = 0, MC_ROLE_INNER = 1, MC_ROLE_ROOT = 2 };
+int mc_colour_trees(int32_t n_nodes, int32_t k_colours, int32_t* parent);
+int mc_rank_roles(int32_t n_nodes, int32_t k_colours, int32_t rank, int32_t* role,
+                  int32_t* n_children, int32_t* children);
+
+/* mc_reduce_update with a role per colour.  A rank is root or inner node of at most one
+ * colour and a leaf of the others (Section 4.2), so what it adds differs by colour: as a leaf
+ * only its own m GPU replicas, as inner node or root those plus one buffer per child; and only
+ * the root holds the complete sum, so only there can the SGD step follow at once -- the other
+ * colours' partial sums go to grad_out (to be pulled by the parent), and their update is a
+ * later call with the broadcast result as the single contribution.
+ *
+ * n_terms:   host, k_colours int32: colour c adds the first n_terms[c] entries of its sequence
+ *            (row c of order, or 0,1,2,.. if order is NULL); 0 <= n_terms[c] <= P; 0 = the
+ *            colour is skipped and nothing in its range is read or written.
+ * do_update: host, k_colours bytes: non-zero = apply the update for colour c (needs weights and
+ *            momentum); zero = only write the sum to grad_out (needs grad_out).
+ * Other arguments, arithmetic and errors as mc_reduce_update; weights / momentum may be NULL
+ * when no colour updates, grad_out may be NULL when every non-skipped colour updates. */
+int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32_t P,
+                           const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
+                           void* grad_out, void* weights, void* momentum,
+                           float lr, float mu, float wd, void* stream);
+
 /* ---- diagnostics and tuning ---------------------------------------------------------- */
 /* Plain device-to-device copy of n_bytes (a multiple of 16; dst and src device, 16-byte
  * aligned, not overlapping) with the library's own 128-bit streaming kernel.  Not part of the
@@ -137,9 +177,9 @@ int mc_last_hip_error(void);           /* raw hipError_t of this thread's last M
  * Returns MC_ERR_INVALID_ARG for an unknown option or a value outside its range. */
 enum {
     MC_OPT_RU_UNROLL = 1,          /* 16-byte vectors per thread per tile in reduce_update: 1 or 2 */
-    MC_OPT_RU_NONTEMPORAL = 2,     /* bit 0: streaming (non-temporal) loads of the contributions;
-                                      bit 1: streaming store of grad_out.  Weights and momentum
-                                      always use the normal policy so that they stay cached. */
+    MC_OPT_RU_NONTEMPORAL = 2,     /* 0 / 1: streaming (non-temporal) loads of the contributions
+                                      and store of grad_out.  Weights and momentum always use
+                                      the normal policy so that they stay cached. */
     MC_OPT_PACK_NONTEMPORAL = 3    /* pack/unpack: bit 0 streaming access to the per-layer
                                       tensors, bit 1 streaming access to the flat payload */
 };

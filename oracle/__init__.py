@@ -54,6 +54,11 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_float, ctypes.c_float, ctypes.c_float]
         lib.mco_reduce_update.restype = ctypes.c_int
+        lib.mco_reduce_update_roles.argtypes = [
+            i64p, ctypes.c_int32, vpp, ctypes.c_int32, i32p, i32p, ctypes.POINTER(ctypes.c_uint8),
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        lib.mco_reduce_update_roles.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -164,3 +169,28 @@ def reduce_update_colour(layout: Layout, c: int, contrib: Sequence[np.ndarray], 
                                      None if g is None else g.ctypes.data,
                                      w.ctypes.data, v.ctypes.data,
                                      ctypes.c_float(lr), ctypes.c_float(mu), ctypes.c_float(wd))
+
+
+def reduce_update_roles(layout: Layout, contrib: Sequence[np.ndarray], n_terms, do_update,
+                        g: np.ndarray, w, v, lr: float, mu: float, wd: float, order=None) -> None:
+    """Per-colour roles (Section 4.2): colour c adds the first n_terms[c] entries of its
+    sequence into ``g`` (IN PLACE; ranges of skipped colours are left alone) and applies the
+    SGD step only where do_update[c] is set.  ``w`` / ``v`` may be None if no colour updates."""
+    P = len(contrib)
+    for p, a in enumerate(contrib):
+        _check_f32(a, layout.N, f"contrib {p}")
+    _check_f32(g, layout.N, "g")
+    nt = np.ascontiguousarray(n_terms, dtype=np.int32)
+    du = np.ascontiguousarray(do_update, dtype=np.uint8)
+    assert nt.shape == (layout.k,) and du.shape == (layout.k,)
+    if w is not None:
+        _check_f32(w, layout.N, "w")
+        _check_f32(v, layout.N, "v")
+    o, optr = _order_arg(order, layout.k, P)
+    rc = _load().mco_reduce_update_roles(
+        _ptr(layout.bounds, ctypes.c_int64), layout.k, _ptr_table(contrib), P, optr,
+        _ptr(nt, ctypes.c_int32), _ptr(du, ctypes.c_uint8), g.ctypes.data,
+        None if w is None else w.ctypes.data, None if v is None else v.ctypes.data,
+        ctypes.c_float(lr), ctypes.c_float(mu), ctypes.c_float(wd))
+    if rc != 0:
+        raise ValueError("mco_reduce_update_roles: invalid argument")

@@ -92,6 +92,48 @@ void mco_reduce_update_colour(int64_t lo, int64_t hi, const float *const *x, int
     }
 }
 
+/* One colour, sum only: what a leaf or inner node of the colour's tree produces (its partial
+ * sum, handed to the parent).  The SGD step needs the complete sum, which only the root has
+ * (Section 4.2: roots and non-leaf nodes sum, leaves only send; the result is broadcast from
+ * the roots afterwards). */
+void mco_reduce_colour(int64_t lo, int64_t hi, const float *const *x, int32_t n_terms,
+                       const int32_t *seq, float *g)
+{
+    for (int64_t i = lo; i < hi; ++i) {
+        float acc = x[seq[0]][i];
+        for (int32_t q = 1; q < n_terms; ++q)
+            acc = acc + x[seq[q]][i];
+        g[i] = acc;
+    }
+}
+
+/* Per-colour roles: colour c adds the first n_terms[c] entries of its sequence (0 = the
+ * colour is skipped, nothing of its range is touched); where do_update[c] is non-zero the
+ * SGD step follows (this rank holds the colour's complete sum), elsewhere only g is written.
+ * order as in mco_reduce_update (NULL = identity).  Returns 0 or -1. */
+int mco_reduce_update_roles(const int64_t *bounds, int32_t k, const float *const *x, int32_t P,
+                            const int32_t *order, const int32_t *n_terms,
+                            const uint8_t *do_update, float *g, float *w, float *v,
+                            float lr, float mu, float wd)
+{
+    if (!bounds || !x || !n_terms || !do_update || k < 1 || P < 1 || P > 64) return -1;
+    int32_t ident[64];
+    for (int32_t q = 0; q < P; ++q) ident[q] = q;
+    for (int32_t c = 0; c < k; ++c) {
+        if (n_terms[c] < 0 || n_terms[c] > P) return -1;
+        if (n_terms[c] == 0) continue;
+        const int32_t *seq = order ? order + (size_t)c * (size_t)P : ident;
+        if (do_update[c]) {
+            if (!w || !v) return -1;
+            mco_reduce_update_colour(bounds[c], bounds[c + 1], x, n_terms[c], seq, g, w, v, lr, mu, wd);
+        } else {
+            if (!g) return -1;
+            mco_reduce_colour(bounds[c], bounds[c + 1], x, n_terms[c], seq, g);
+        }
+    }
+    return 0;
+}
+
 /* All colours, in index order.  order is k*P row-major (row c = sequence of colour c) or
  * NULL for the identity sequence 0,1,..,P-1 in every colour.  Returns 0 or -1. */
 int mco_reduce_update(const int64_t *bounds, int32_t k, const float *const *x, int32_t P,

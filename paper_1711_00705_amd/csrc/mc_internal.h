@@ -12,7 +12,10 @@
 namespace mc {
 
 // Elements of the flat payload that one workgroup of the pack / unpack kernels covers.
-constexpr int64_t kPackTileElems = 4096;
+#ifndef MC_PACK_TILE_ELEMS
+#define MC_PACK_TILE_ELEMS 2048
+#endif
+constexpr int64_t kPackTileElems = MC_PACK_TILE_ELEMS;
 // Device pointers that fit in one pack / unpack launch's kernel-argument block.
 constexpr int kPackMaxPtrs = 256;
 constexpr int kMaxDevices = 16;

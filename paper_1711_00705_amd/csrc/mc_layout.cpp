@@ -10,8 +10,8 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 std::atomic<int> g_ru_unroll{2};
-std::atomic<int> g_ru_nontemporal{3};
-std::atomic<int> g_pack_nontemporal{0};
+std::atomic<int> g_ru_nontemporal{1};
+std::atomic<int> g_pack_nontemporal{3};
 
 }  // namespace
 
@@ -129,7 +129,7 @@ int mc_set_option(int option, int value) {
             g_ru_unroll.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_RU_NONTEMPORAL:
-            if (value < 0 || value > 3) return MC_ERR_INVALID_ARG;
+            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
             g_ru_nontemporal.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_PACK_NONTEMPORAL:

@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <vector>
 
 #include "mc_internal.h"
 
@@ -25,12 +26,13 @@ constexpr int kMaxSegs = 32;     // colours per launch
 constexpr int kPtrSlots = 256;   // permuted contribution pointers per launch (kMaxSegs*P <= this)
 
 struct RuArgs {
-    const float* x[kPtrSlots];      // x[s*P + q]: q-th term of segment s
-    int64_t bound[kMaxSegs + 1];    // segment s covers flat elements [bound[s], bound[s+1])
+    const float* x[kPtrSlots];      // x[s*np + q]: q-th term of segment s (np terms per segment)
+    int64_t lo[kMaxSegs];           // segment s covers flat elements [lo[s], hi[s])
+    int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
     int32_t n_segs;
-    float* g;                       // may be null
-    float* w;
+    float* g;                       // may be null when UPDATE
+    float* w;                       // unused when !UPDATE
     float* v;
     float lr, mu, wd;
 };
@@ -72,16 +74,21 @@ __device__ __forceinline__ void sgd(float g, float& w, float& v, float lr, float
 }
 
 // P > 0: compile-time number of terms; P == 0: run-time count in `Prt` (up to MC_MAX_P).
-template <int P, int U, int THREADS, bool HAS_G, bool NT_IN, bool NT_G>
+// UPDATE: the SGD step follows the sum (the rank holds the complete sum of these colours);
+// otherwise only the sum is written to g and w, v are never touched.
+// NT: streaming (non-temporal) loads of the contributions and store of g.
+template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool NT>
 __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Prt) {
+    static_assert(HAS_G || UPDATE, "a launch must produce something");
+    constexpr bool NT_IN = NT, NT_G = NT;
     constexpr int64_t kTile = int64_t(THREADS) * 4 * U;
     const int np = P > 0 ? P : Prt;
 
     // blockIdx -> (segment, tile); a handful of scalar compares.
     int s = 0;
     while (s + 1 < a.n_segs && int(blockIdx.x) >= a.first_block[s + 1]) ++s;
-    const int64_t lo = a.bound[s];
-    const int64_t hi = a.bound[s + 1];
+    const int64_t lo = a.lo[s];
+    const int64_t hi = a.hi[s];
     const int64_t base = lo + int64_t(int(blockIdx.x) - a.first_block[s]) * kTile;
     const float* const* xs = a.x + s * np;
 
@@ -97,10 +104,12 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
             for (int q = 0; q < P; ++q)
 #pragma unroll
                 for (int u = 0; u < U; ++u) t[q][u] = load4<NT_IN>(xs[q] + idx[u]);
+            if (UPDATE) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                wv[u] = *reinterpret_cast<const float4*>(a.w + idx[u]);
-                vv[u] = *reinterpret_cast<const float4*>(a.v + idx[u]);
+                for (int u = 0; u < U; ++u) {
+                    wv[u] = *reinterpret_cast<const float4*>(a.w + idx[u]);
+                    vv[u] = *reinterpret_cast<const float4*>(a.v + idx[u]);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -116,8 +125,10 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                wv[u] = *reinterpret_cast<const float4*>(a.w + idx[u]);
-                vv[u] = *reinterpret_cast<const float4*>(a.v + idx[u]);
+                if (UPDATE) {
+                    wv[u] = *reinterpret_cast<const float4*>(a.w + idx[u]);
+                    vv[u] = *reinterpret_cast<const float4*>(a.v + idx[u]);
+                }
                 acc[u] = load4<NT_IN>(xs[0] + idx[u]);
             }
             for (int q = 1; q < np; ++q) {
@@ -135,12 +146,14 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (HAS_G) store4<NT_G>(a.g + idx[u], acc[u]);
-            sgd(acc[u].x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
-            sgd(acc[u].y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
-            sgd(acc[u].z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
-            sgd(acc[u].w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
-            *reinterpret_cast<float4*>(a.w + idx[u]) = wv[u];
-            *reinterpret_cast<float4*>(a.v + idx[u]) = vv[u];
+            if (UPDATE) {
+                sgd(acc[u].x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
+                sgd(acc[u].y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
+                sgd(acc[u].z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
+                sgd(acc[u].w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
+                *reinterpret_cast<float4*>(a.w + idx[u]) = wv[u];
+                *reinterpret_cast<float4*>(a.v + idx[u]) = vv[u];
+            }
         }
         return;
     }
@@ -159,69 +172,78 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
                 acc.z = acc.z + t.z;
                 acc.w = acc.w + t.w;
             }
-            float4 wq = *reinterpret_cast<const float4*>(a.w + i);
-            float4 vq = *reinterpret_cast<const float4*>(a.v + i);
             if (HAS_G) *reinterpret_cast<float4*>(a.g + i) = acc;
-            sgd(acc.x, wq.x, vq.x, a.lr, a.mu, a.wd);
-            sgd(acc.y, wq.y, vq.y, a.lr, a.mu, a.wd);
-            sgd(acc.z, wq.z, vq.z, a.lr, a.mu, a.wd);
-            sgd(acc.w, wq.w, vq.w, a.lr, a.mu, a.wd);
-            *reinterpret_cast<float4*>(a.w + i) = wq;
-            *reinterpret_cast<float4*>(a.v + i) = vq;
+            if (UPDATE) {
+                float4 wq = *reinterpret_cast<const float4*>(a.w + i);
+                float4 vq = *reinterpret_cast<const float4*>(a.v + i);
+                sgd(acc.x, wq.x, vq.x, a.lr, a.mu, a.wd);
+                sgd(acc.y, wq.y, vq.y, a.lr, a.mu, a.wd);
+                sgd(acc.z, wq.z, vq.z, a.lr, a.mu, a.wd);
+                sgd(acc.w, wq.w, vq.w, a.lr, a.mu, a.wd);
+                *reinterpret_cast<float4*>(a.w + i) = wq;
+                *reinterpret_cast<float4*>(a.v + i) = vq;
+            }
         } else {
             for (int64_t e = i; e < hi; ++e) {
                 float acc = xs[0][e];
                 for (int q = 1; q < np; ++q) acc = acc + xs[q][e];
-                float we = a.w[e], ve = a.v[e];
                 if (HAS_G) a.g[e] = acc;
-                sgd(acc, we, ve, a.lr, a.mu, a.wd);
-                a.w[e] = we;
-                a.v[e] = ve;
+                if (UPDATE) {
+                    float we = a.w[e], ve = a.v[e];
+                    sgd(acc, we, ve, a.lr, a.mu, a.wd);
+                    a.w[e] = we;
+                    a.v[e] = ve;
+                }
             }
         }
     }
 }
 
-template <int P, int U, bool HAS_G>
-void launch_nt(int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
+template <int P, int U>
+void launch_variant(bool update, bool nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
     constexpr int T = kThreads;
-    switch (nt & 3) {
-        case 0: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, false, false>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
-        case 1: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, true, false>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
-        case 2: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, false, true>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
-        default: hipLaunchKernelGGL((reduce_update_kernel<P, U, T, HAS_G, true, true>), dim3(blocks), dim3(T), 0, s, a, Prt); break;
+    const dim3 grid(blocks), block(T);
+#define MC_RU_LAUNCH(G, UPD, NT) \
+    hipLaunchKernelGGL((reduce_update_kernel<P, U, T, G, UPD, NT>), grid, block, 0, s, a, Prt)
+    if (!update) {
+        if (nt) MC_RU_LAUNCH(true, false, true); else MC_RU_LAUNCH(true, false, false);
+    } else if (a.g) {
+        if (nt) MC_RU_LAUNCH(true, true, true); else MC_RU_LAUNCH(true, true, false);
+    } else {
+        if (nt) MC_RU_LAUNCH(false, true, true); else MC_RU_LAUNCH(false, true, false);
     }
+#undef MC_RU_LAUNCH
 }
 
 template <int P>
-void launch_unroll(int unroll, int nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    if (unroll == 1) {
-        if (a.g) launch_nt<P, 1, true>(nt, blocks, s, a, Prt); else launch_nt<P, 1, false>(nt, blocks, s, a, Prt);
-    } else {
-        if (a.g) launch_nt<P, 2, true>(nt, blocks, s, a, Prt); else launch_nt<P, 2, false>(nt, blocks, s, a, Prt);
-    }
+void launch_unroll(int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
+    if (unroll == 1)
+        launch_variant<P, 1>(update, nt, blocks, s, a, Prt);
+    else
+        launch_variant<P, 2>(update, nt, blocks, s, a, Prt);
 }
 
-void launch(int P, int unroll, int nt, unsigned blocks, hipStream_t s, const RuArgs& a) {
+void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const RuArgs& a) {
     switch (P) {
-        case 1: launch_unroll<1>(unroll, nt, blocks, s, a, P); break;
-        case 2: launch_unroll<2>(unroll, nt, blocks, s, a, P); break;
-        case 3: launch_unroll<3>(unroll, nt, blocks, s, a, P); break;
-        case 4: launch_unroll<4>(unroll, nt, blocks, s, a, P); break;
-        case 5: launch_unroll<5>(unroll, nt, blocks, s, a, P); break;
-        case 6: launch_unroll<6>(unroll, nt, blocks, s, a, P); break;
-        case 7: launch_unroll<7>(unroll, nt, blocks, s, a, P); break;
-        case 8: launch_unroll<8>(unroll, nt, blocks, s, a, P); break;
-        default: launch_unroll<0>(unroll, nt, blocks, s, a, P); break;
+        case 1: launch_unroll<1>(unroll, update, nt, blocks, s, a, P); break;
+        case 2: launch_unroll<2>(unroll, update, nt, blocks, s, a, P); break;
+        case 3: launch_unroll<3>(unroll, update, nt, blocks, s, a, P); break;
+        case 4: launch_unroll<4>(unroll, update, nt, blocks, s, a, P); break;
+        case 5: launch_unroll<5>(unroll, update, nt, blocks, s, a, P); break;
+        case 6: launch_unroll<6>(unroll, update, nt, blocks, s, a, P); break;
+        case 7: launch_unroll<7>(unroll, update, nt, blocks, s, a, P); break;
+        case 8: launch_unroll<8>(unroll, update, nt, blocks, s, a, P); break;
+        default: launch_unroll<0>(unroll, update, nt, blocks, s, a, P); break;
     }
 }
 
-}  // namespace
-
-extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P,
-                                const int32_t* order, void* grad_out, void* weights,
-                                void* momentum, float lr, float mu, float wd, void* stream) {
+// Shared by both entry points.  n_terms / do_update are null for the uniform call (every
+// colour adds all P terms and updates).
+int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
+        const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
+        void* momentum, float lr, float mu, float wd, void* stream) {
     if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if ((n_terms == nullptr) != (do_update == nullptr)) return MC_ERR_INVALID_ARG;
     if (order) {
         for (int32_t c = 0; c < L->k; ++c) {
             uint64_t seen = 0;
@@ -232,8 +254,17 @@ extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, 
             }
         }
     }
+    bool any_update = n_terms == nullptr, any_sum_only = false;
+    if (n_terms) {
+        for (int32_t c = 0; c < L->k; ++c) {
+            if (n_terms[c] < 0 || n_terms[c] > P) return MC_ERR_INVALID_ARG;
+            if (n_terms[c] == 0 || L->bounds[c + 1] == L->bounds[c]) continue;
+            if (do_update[c]) any_update = true; else any_sum_only = true;
+        }
+    }
     if (L->N == 0) return MC_OK;
-    if (!weights || !momentum) return MC_ERR_INVALID_ARG;
+    if (any_update && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
+    if (any_sum_only && !grad_out) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
         if (!contrib[p]) return MC_ERR_INVALID_ARG;
 
@@ -241,8 +272,8 @@ extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, 
     const void* bufs[MC_MAX_P + 3];
     int nb = 0;
     for (int32_t p = 0; p < P; ++p) bufs[nb++] = contrib[p];
-    bufs[nb++] = weights;
-    bufs[nb++] = momentum;
+    if (weights) bufs[nb++] = weights;
+    if (momentum) bufs[nb++] = momentum;
     if (grad_out) bufs[nb++] = grad_out;
     for (int i = 0; i < nb; ++i)
         if (!mc::aligned(bufs[i], 16)) return MC_ERR_ALIGN;
@@ -252,10 +283,8 @@ extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, 
             if (mc::overlaps(bufs[i], bytes, bufs[j], bytes)) return MC_ERR_OVERLAP;
 
     const int unroll = mc::option(MC_OPT_RU_UNROLL);
-    const int threads = kThreads;
-    const int nt = mc::option(MC_OPT_RU_NONTEMPORAL);
-    const int64_t tile = int64_t(threads) * 4 * unroll;
-    const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / P);
+    const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
+    const int64_t tile = int64_t(kThreads) * 4 * unroll;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     RuArgs a;
@@ -265,42 +294,81 @@ extern "C" int mc_reduce_update(const mc_layout* L, const void* const* contrib, 
     a.lr = lr;
     a.mu = mu;
     a.wd = wd;
-    int32_t c = 0;
-    while (c < L->k) {
-        // Gather the next run of non-empty colours into one launch.
-        int ns = 0;
-        int64_t blocks = 0;
-        a.first_block[0] = 0;
-        while (c < L->k && ns < segs_per_launch) {
-            const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
-            if (hi > lo) {
-                if (ns > 0 && a.bound[ns] != lo) break;  // (cannot happen: colours are contiguous)
+
+    // Colours that add the same number of terms and agree on updating share launches (a rank is
+    // inner node or root for at most one colour, so there are at most two such classes in
+    // practice; the uniform call has one).  `done` marks colours already launched.
+    std::vector<uint8_t> done(size_t(L->k), 0);
+    for (int32_t c0 = 0; c0 < L->k; ++c0) {
+        if (done[c0]) continue;
+        const int32_t cnt = n_terms ? n_terms[c0] : P;
+        const bool upd = do_update ? do_update[c0] != 0 : true;
+        if (cnt == 0 || L->bounds[c0 + 1] == L->bounds[c0]) {
+            done[c0] = 1;
+            continue;
+        }
+        const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / cnt);
+        int32_t c = c0;
+        while (c < L->k) {
+            int ns = 0;
+            int64_t blocks = 0;
+            a.first_block[0] = 0;
+            for (; c < L->k && ns < segs_per_launch; ++c) {
+                if (done[c]) continue;
+                const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
+                const int32_t cc = n_terms ? n_terms[c] : P;
+                const bool cu = do_update ? do_update[c] != 0 : true;
+                if (cc == 0 || hi == lo) {
+                    done[c] = 1;
+                    continue;
+                }
+                if (cc != cnt || cu != upd) continue;  // another class: a later pass takes it
                 const int64_t nblk = (hi - lo + tile - 1) / tile;
                 if (blocks + nblk > 0x7fffffff) {
                     if (ns == 0) return MC_ERR_INVALID_ARG;
                     break;
                 }
-                a.bound[ns] = lo;
-                a.bound[ns + 1] = hi;
-                for (int32_t q = 0; q < P; ++q) {
+                a.lo[ns] = lo;
+                a.hi[ns] = hi;
+                for (int32_t q = 0; q < cnt; ++q) {
                     const int32_t src = order ? order[size_t(c) * P + q] : q;
-                    a.x[ns * P + q] = static_cast<const float*>(contrib[src]);
+                    a.x[ns * cnt + q] = static_cast<const float*>(contrib[src]);
                 }
                 blocks += nblk;
                 a.first_block[ns + 1] = int32_t(blocks);
+                done[c] = 1;
                 ++ns;
             }
-            ++c;
+            if (ns == 0) break;
+            for (int i = ns * cnt; i < kPtrSlots; ++i) a.x[i] = nullptr;
+            for (int i = ns; i < kMaxSegs; ++i) {
+                a.lo[i] = a.hi[i] = 0;
+                a.first_block[i + 1] = a.first_block[ns];
+            }
+            a.n_segs = ns;
+            launch(cnt, unroll, upd, nt, unsigned(blocks), s, a);
+            MC_HIP_TRY(hipGetLastError());
         }
-        if (ns == 0) continue;
-        for (int i = ns * P; i < kPtrSlots; ++i) a.x[i] = nullptr;
-        for (int i = ns + 1; i <= kMaxSegs; ++i) {
-            a.bound[i] = a.bound[ns];
-            a.first_block[i] = a.first_block[ns];
-        }
-        a.n_segs = ns;
-        launch(P, unroll, nt, unsigned(blocks), s, a);
-        MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
 }
+
+}  // namespace
+
+extern "C" {
+
+int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
+                     void* grad_out, void* weights, void* momentum, float lr, float mu, float wd,
+                     void* stream) {
+    return run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, lr, mu, wd, stream);
+}
+
+int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32_t P,
+                           const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
+                           void* grad_out, void* weights, void* momentum, float lr, float mu,
+                           float wd, void* stream) {
+    if (!n_terms || !do_update) return MC_ERR_INVALID_ARG;
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, lr, mu, wd, stream);
+}
+
+}  // extern "C"

@@ -25,6 +25,7 @@ COLOUR_ALIGN_ELEMS = 256
 OPT_RU_UNROLL = 1
 OPT_RU_NONTEMPORAL = 2
 OPT_PACK_NONTEMPORAL = 3
+ROLE_LEAF, ROLE_INNER, ROLE_ROOT = 0, 1, 2
 
 _i64p = ctypes.POINTER(ctypes.c_int64)
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -44,6 +45,11 @@ SIGNATURES = {
     "mc_unpack": (ctypes.c_int, [_vp, _vp, _vpp, _vp]),
     "mc_reduce_update": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
                                         ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_colour_trees": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, _i32p]),
+    "mc_rank_roles": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p]),
+    "mc_reduce_update_roles": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
+                                              ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp,
+                                              ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
     "mc_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_int64, _vp]),
     "mc_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "mc_last_hip_error": (ctypes.c_int, []),
@@ -52,8 +58,29 @@ SIGNATURES = {
 }
 
 
+def _share_torch_hip_runtime() -> None:
+    """One process must use ONE HIP runtime.  PyTorch wheels bundle their own libamdhip64
+    (same SONAME as the system one, found through torch/lib's RPATH).  If libmc.so pulled in
+    the system copy first and torch its bundled copy later, the process would hold two
+    runtimes and the second one sees no device.  Device memory and streams come from torch,
+    so when torch is installed its copy is loaded here, before libmc.so, whose dependency on
+    the SONAME then binds to it; a later `import torch` finds the same file already mapped."""
+    import importlib.util
+    import os
+    try:
+        spec = importlib.util.find_spec("torch")
+    except (ImportError, ValueError):
+        spec = None
+    if spec is None or not spec.origin:
+        return
+    cand = os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+
+
 def _load() -> ctypes.CDLL:
     path = _build.library_path(build_if_missing=True)
+    _share_torch_hip_runtime()
     lib = ctypes.CDLL(path)
     for name, (res, args) in SIGNATURES.items():
         fn = getattr(lib, name)          # AttributeError if the symbol is not exported
@@ -170,6 +197,46 @@ def reduce_update(layout: Layout, contrib_ptrs: Sequence[Optional[int]], order, 
         optr = o.ctypes.data_as(_i32p)
     _check(lib.mc_reduce_update(layout.handle, _ptr_table(contrib_ptrs), P, optr, grad_out_ptr,
                                 weights_ptr, momentum_ptr, lr, mu, wd, stream or None), "mc_reduce_update")
+
+
+def reduce_update_roles(layout: Layout, contrib_ptrs, order, n_terms, do_update,
+                        grad_out_ptr: Optional[int], weights_ptr: Optional[int],
+                        momentum_ptr: Optional[int], lr: float, mu: float, wd: float,
+                        stream: int = 0) -> None:
+    P = _count(contrib_ptrs)
+    optr = None
+    if order is not None:
+        o = np.ascontiguousarray(order, dtype=np.int32)
+        if o.size != layout.k * P:
+            raise ValueError("order must hold k_colours * P entries")
+        optr = o.ctypes.data_as(_i32p)
+    nt = np.ascontiguousarray(n_terms, dtype=np.int32)
+    du = np.ascontiguousarray(do_update, dtype=np.uint8)
+    if nt.size != layout.k or du.size != layout.k:
+        raise ValueError("n_terms and do_update must hold k_colours entries")
+    _check(lib.mc_reduce_update_roles(layout.handle, _ptr_table(contrib_ptrs), P, optr,
+                                      nt.ctypes.data_as(_i32p),
+                                      du.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+                                      grad_out_ptr, weights_ptr, momentum_ptr, lr, mu, wd,
+                                      stream or None), "mc_reduce_update_roles")
+
+
+def colour_trees(n_nodes: int, k_colours: int) -> np.ndarray:
+    """parent[c, r] of every node r in every colour's tree (-1 = root)."""
+    out = np.empty((max(k_colours, 0), max(n_nodes, 0)), dtype=np.int32)
+    _check(lib.mc_colour_trees(n_nodes, k_colours, out.ctypes.data_as(_i32p)), "mc_colour_trees")
+    return out
+
+
+def rank_roles(n_nodes: int, k_colours: int, rank: int):
+    """(role[k], n_children[k], children[k, k]) of one rank."""
+    k = max(k_colours, 0)
+    role = np.empty(k, dtype=np.int32)
+    cnt = np.empty(k, dtype=np.int32)
+    ch = np.empty((k, k), dtype=np.int32)
+    _check(lib.mc_rank_roles(n_nodes, k_colours, rank, role.ctypes.data_as(_i32p),
+                             cnt.ctypes.data_as(_i32p), ch.ctypes.data_as(_i32p)), "mc_rank_roles")
+    return role, cnt, ch
 
 
 def copy(dst_ptr: Optional[int], src_ptr: Optional[int], n_bytes: int, stream: int = 0) -> None:

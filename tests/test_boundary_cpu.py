@@ -22,7 +22,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
-    assert len(names) >= 15
+    assert len(names) >= 18
     raw = ctypes.CDLL(mc.LIBRARY_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in mc.h but not exported"
@@ -155,7 +155,7 @@ def test_empty_payload_is_a_no_op():
 def test_options():
     assert mc.get_option(mc.OPT_RU_UNROLL) in (1, 2)
     for opt, good, bad in ((mc.OPT_RU_UNROLL, (1, 2), (0, 3, 4)),
-                           (mc.OPT_RU_NONTEMPORAL, (0, 1, 2, 3), (-1, 4)),
+                           (mc.OPT_RU_NONTEMPORAL, (0, 1), (-1, 2)),
                            (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4))):
         keep = mc.get_option(opt)
         for g in good:
@@ -177,3 +177,40 @@ def test_copy_rejects_before_launch():
     assert _code(mc.copy, B, None, 1024) == mc.ERR_INVALID_ARG
     assert _code(mc.copy, B + 8, B + 4096, 1024) == mc.ERR_ALIGN
     assert _code(mc.copy, B, B + 512, 1024) == mc.ERR_OVERLAP
+
+
+def test_reduce_update_roles_rejects_before_launch():
+    L = mc.Layout([1000, 24], 2)
+    B = 0x10000000
+    x = [B + (i << 20) for i in range(4)]
+    g, w, v = B + (8 << 20), B + (9 << 20), B + (10 << 20)
+    rr = mc.reduce_update_roles
+    assert _code(rr, L, x, None, [4, 5], [1, 1], g, w, v, .1, .9, 0.) == mc.ERR_INVALID_ARG   # n_terms > P
+    assert _code(rr, L, x, None, [4, -1], [1, 1], g, w, v, .1, .9, 0.) == mc.ERR_INVALID_ARG
+    assert _code(rr, L, x, None, [4, 2], [1, 0], None, w, v, .1, .9, 0.) == mc.ERR_INVALID_ARG  # sum-only needs g
+    assert _code(rr, L, x, None, [4, 2], [1, 0], g, None, v, .1, .9, 0.) == mc.ERR_INVALID_ARG  # update needs w
+    assert _code(rr, L, x, None, [4, 2], [1, 0], g, w, None, .1, .9, 0.) == mc.ERR_INVALID_ARG
+    assert _code(rr, L, x, None, [4, 2], [1, 0], g + 4, w, v, .1, .9, 0.) == mc.ERR_ALIGN
+    assert _code(rr, L, x, None, [4, 2], [1, 0], x[0], w, v, .1, .9, 0.) == mc.ERR_OVERLAP
+    rc = mc.lib.mc_reduce_update_roles(L.handle, mc.ptr_table(x), 4, None, None, None, g, w, v, 0., 0., 0., None)
+    assert rc == mc.ERR_INVALID_ARG
+    # every colour skipped: nothing to do, nothing needed
+    assert _code(rr, L, x, None, [0, 0], [1, 0], None, None, None, .1, .9, 0.) in (mc.OK, mc.ERR_HIP)
+
+
+@pytest.mark.parametrize("first", ["torch", "mc"])
+def test_one_hip_runtime_whatever_the_import_order(first):
+    """torch bundles its own HIP runtime; the binding must end up sharing it, or the second
+    runtime in the process would see no device."""
+    import subprocess
+    import sys
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "%s\n"
+        "libs = sorted(set(l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l))\n"
+        "print(len(libs), libs)\n"
+    ) % (ROOT, "import torch; from paper_1711_00705_amd import mc" if first == "torch"
+         else "from paper_1711_00705_amd import mc; import torch")
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.split()[0] == "1", out.stdout

@@ -52,7 +52,7 @@ def test_tiny_config(order_kind, misalign):
 
 
 @pytest.mark.parametrize("unroll", [1, 2])
-@pytest.mark.parametrize("nt", [0, 1, 2, 3])
+@pytest.mark.parametrize("nt", [0, 1])
 @pytest.mark.parametrize("pack_nt", [0, 1, 2, 3])
 def test_launch_shapes_do_not_change_bits(unroll, nt, pack_nt):
     mc.set_option(mc.OPT_RU_UNROLL, unroll)
