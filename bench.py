@@ -2,16 +2,18 @@
 """Benchmark of the per-rank multi-colour reduce + SGD update step on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic gradients that are
-already resident in HBM as per-layer tensors:
-    P x mc_pack (per-layer tensors -> flat colour-chunked payload)
-    1 x mc_reduce_update (per-colour fixed-order sum fused with the SGD update, writes g)
-    1 x mc_unpack (updated weights -> per-layer tensors)
+already resident in HBM as per-layer tensors.  Two equivalent forms are timed:
+  fused (default, the headline):  1 x mc_fused_step -- contributions read straight from the
+      per-layer tensors, per-layer weights and momentum updated in place, flat g written;
+  staged:  P x mc_pack (per-layer tensors -> flat colour-chunked payload)
+           1 x mc_reduce_update (per-colour fixed-order sum fused with the SGD update, writes g)
+           1 x mc_unpack (updated weights -> per-layer tensors)
 The layout (a1) is built once per model, like the framework's flattening of its parameters;
 its cost is reported separately as `layout_create_ms`.
 
 Prints ONE JSON line.  `value` is algorithmic bytes of the whole step / wall time of the
-step; `roofline` is for the dominant kernel (reduce_update), timed with events on the
-stream it is launched on, inside the timed region; `cpu_baseline` is the CPU oracle timed
+step; `roofline` is for the dominant kernel (fused_step_kernel, or reduce_update_kernel with
+--path staged), timed with events on the stream it is launched on, inside the timed region; `cpu_baseline` is the CPU oracle timed
 on this machine's host cores on the same workload.
 """
 import argparse
@@ -31,10 +33,10 @@ HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 METRIC = "effective HBM GB/s (% of MI355X peak) and ms per ResNet-50-shaped reduce+update"
 
 
-def measured_traffic(workload, P, k):
-    """HBM-side bytes per reduce_update launch from the rocprofv3 counter runs whose summary
-    is kept under profiles/ (None when there is none for this workload)."""
-    path = os.path.join(ROOT, "profiles", f"reduce_update_{workload}_P{P}_k{k}.txt")
+def measured_traffic(kernel, workload, P, k):
+    """HBM-side bytes per launch of the dominant kernel, from the rocprofv3 counter runs whose
+    summary is kept under profiles/ (None when there is none for this kernel and workload)."""
+    path = os.path.join(ROOT, "profiles", f"{kernel.replace('_kernel', '')}_{workload}_P{P}_k{k}.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -54,6 +56,8 @@ def parse():
     ap.add_argument("--sets", type=int, default=0,
                     help="rotating sets of contribution tensors (0 = pick so that no step re-reads a cached set)")
     ap.add_argument("--order", default="rotation", choices=["identity", "rotation"])
+    ap.add_argument("--path", default="fused", choices=["fused", "staged"],
+                    help="fused: one mc_fused_step per step; staged: P packs + reduce_update + unpack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--kernel-only", action="store_true",
@@ -61,12 +65,13 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref):
-    """The oracle as it stands: whole step (P packs, reduce+update, unpack) on host cores."""
+def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, step_bytes):
+    """The oracle as it stands: whole step (P packs, reduce+update, unpack) on host cores.
+    Its GB/s uses the same step_bytes as the GPU figure beside it, so that the ratio of the
+    two values is the ratio of the step times."""
     import oracle
     O = oracle.Layout(cfg.sizes, cfg.k)
     N = O.N
-    step_bytes = (8 * cfg.P + 4 * (cfg.P + 5) + 8) * N
     w = oracle.pack(O, w_layers_host)
     v = np.zeros(N, np.float32)
 
@@ -166,7 +171,7 @@ def main():
 
     # ---- inputs: seeded, host-generated, uploaded as separate per-layer tensors ------------
     host_sets = []            # kept for the CPU baseline (first 3 sets only)
-    dev_sets, tables = [], []
+    dev_sets, tables, tsets = [], [], []
     for s in range(n_sets):
         per_p = [wl.contribution_tensors(cfg.sizes, p, step=s, heavy_tail=cfg.heavy_tail) for p in range(P)]
         if s < 3:
@@ -174,18 +179,27 @@ def main():
         dev = [upload(ts) for ts in per_p]
         dev_sets.append(dev)
         tables.append([mc.ptr_table([t.data_ptr() for t in d]) for d in dev])
+        tsets.append(mc.set_table([mc.TensorSet(L, [t.data_ptr() for t in d]) for d in dev]))
     w_layers_host = wl.weight_tensors(cfg.sizes)
+    g = torch.empty(N, dtype=torch.float32, device="cuda")
+
+    # staged path state: flat w, v (master), per-layer weights as the unpack destination
     w_layers = upload(w_layers_host)
     w_table = mc.ptr_table([t.data_ptr() for t in w_layers])
     flats = [torch.empty(N, dtype=torch.float32, device="cuda") for _ in range(P)]
     flat_table = mc.ptr_table([f.data_ptr() for f in flats])
     w = torch.empty(N, dtype=torch.float32, device="cuda")
     v = torch.zeros(N, dtype=torch.float32, device="cuda")
-    g = torch.empty(N, dtype=torch.float32, device="cuda")
     mc.pack(L, w_table, w.data_ptr(), sh)
+
+    # fused path state: per-layer weights and momentum, updated in place
+    fw_layers = upload(w_layers_host)
+    fv_layers = [torch.zeros_like(t) for t in fw_layers]
+    fw_set = mc.TensorSet(L, [t.data_ptr() for t in fw_layers])
+    fv_set = mc.TensorSet(L, [t.data_ptr() for t in fv_layers])
     torch.cuda.synchronize()
 
-    def step(i, ev=None):
+    def staged_step(i, ev=None):
         tabs = tables[i % n_sets]
         for p in range(P):
             mc.pack(L, tabs[p], flats[p].data_ptr(), sh)
@@ -197,55 +211,88 @@ def main():
             ev[1].record(stream)
         mc.unpack(L, w.data_ptr(), w_table, sh)
 
-    # ---- parity of the very first step against the oracle (same host bytes) ----------------
+    def fused_step(i, ev=None):
+        if ev is not None:
+            ev[0].record(stream)
+        mc.fused_step(L, tsets[i % n_sets], order, g.data_ptr(), fw_set, fv_set, cfg.lr, cfg.mu, cfg.wd, sh)
+        if ev is not None:
+            ev[1].record(stream)
+
+    fused = args.path == "fused"
+    step = fused_step if fused else staged_step
+    kernel_name = "fused_step_kernel" if fused else "reduce_update_kernel"
+    kernel_bytes = 4 * (P + 5) * N        # P reads + w, v read and written + g written: same for both kernels
+    step_bytes = kernel_bytes if fused else (8 * P + 4 * (P + 5) + 8) * N
+
+    # ---- parity of the very first step of BOTH paths against the oracle (same host bytes) ----
     parity_ref, cpu = {}, None
-    step(0)
+    staged_step(0)
     torch.cuda.synchronize()
     first = dict(g=g.cpu().numpy(), w=w.cpu().numpy(), v=v.cpu().numpy())
+    fused_step(0)
+    torch.cuda.synchronize()
+    first_fused = dict(g=g.cpu().numpy(), w=[t.cpu().numpy() for t in fw_layers],
+                       v=[t.cpu().numpy() for t in fv_layers])
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, order, host_sets, w_layers_host, args.cpu_seconds, parity_ref)
-        for key in ("g", "w", "v"):
-            a = first[key].view(np.uint32)
-            b = parity_ref[key].view(np.uint32)
-            if not np.array_equal(a, b):
-                print(f"bench.py: PARITY FAILURE on {key}: {int((a != b).sum())} words differ", file=sys.stderr)
-                sys.exit(4)
+        cpu = cpu_baseline(cfg, order, host_sets, w_layers_host, args.cpu_seconds, parity_ref, step_bytes)
+        import oracle
+        O = oracle.Layout(cfg.sizes, k)
+        ref_layers = dict(w=oracle.unpack(O, parity_ref["w"]), v=oracle.unpack(O, parity_ref["v"]))
+        bad = [key for key in ("g", "w", "v")
+               if not np.array_equal(first[key].view(np.uint32), parity_ref[key].view(np.uint32))]
+        if not np.array_equal(first_fused["g"].view(np.uint32), parity_ref["g"].view(np.uint32)):
+            bad.append("fused g")
+        for key in ("w", "v"):
+            for a, b in zip(first_fused[key], ref_layers[key]):
+                if not np.array_equal(a.view(np.uint32), b.view(np.uint32)):
+                    bad.append("fused " + key)
+                    break
+        if bad:
+            print(f"bench.py: PARITY FAILURE against the oracle on {bad}", file=sys.stderr)
+            sys.exit(4)
     host_sets = None
+
+    def kernel_launch(i):
+        if fused:
+            mc.fused_step(L, tsets[i % n_sets], order, g.data_ptr(), fw_set, fv_set, cfg.lr, cfg.mu, cfg.wd, sh)
+        else:
+            mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                             cfg.lr, cfg.mu, cfg.wd, sh)
 
     if args.kernel_only:
         for i in range(args.warmup):
-            mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
-                             cfg.lr, cfg.mu, cfg.wd, sh)
+            kernel_launch(i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
-            mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
-                             cfg.lr, cfg.mu, cfg.wd, sh)
+            kernel_launch(args.warmup + i)
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / args.steps
         # known-size traffic for counter calibration: copy_kernel moves copy_bytes each way
         copy_bytes = (N // 4) * 16
         for i in range(3):
-            mc.copy(flats[0].data_ptr(), flats[1 % P].data_ptr() if P > 1 else g.data_ptr(), copy_bytes, sh)
+            mc.copy(flats[0].data_ptr(), g.data_ptr(), copy_bytes, sh)
         torch.cuda.synchronize()
-        print(json.dumps({"kernel_only_ms": ms, "GBps": 4 * (P + 5) * N / ms / 1e6,
-                          "reduce_update_bytes": 4 * (P + 5) * N, "copy_bytes_each_way": copy_bytes}))
+        print(json.dumps({"kernel": kernel_name, "kernel_only_ms": ms, "GBps": kernel_bytes / ms / 1e6,
+                          "kernel_bytes": kernel_bytes, "copy_bytes_each_way": copy_bytes}))
         return
 
-    # ---- warm-up, then EXACTLY K timed steps ------------------------------------------------
-    for i in range(args.warmup):
-        step(i + 1)
-    torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + 1 + i, events[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    ru_ms = np.array([a.elapsed_time(b) for a, b in events])
+    def timed_steps(fn, warmup, steps):
+        """W untimed steps, then EXACTLY `steps` timed ones; events bracket the dominant kernel."""
+        for i in range(warmup):
+            fn(i + 1)
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(warmup + 1 + i, events[i])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall * 1e3 / steps, np.array([a.elapsed_time(b) for a, b in events])
+
+    ms_per_step, k_ms = timed_steps(step, args.warmup, args.steps)
+    other_ms, other_k_ms = timed_steps(staged_step if fused else fused_step, args.warmup, args.steps)
 
     # ---- the pieces on their own (events around back-to-back launches), and the copy yardstick
     def timed(fn, reps):
@@ -265,10 +312,11 @@ def main():
     unpack_ms = timed(lambda r: mc.unpack(L, w.data_ptr(), w_table, sh), reps)
     copy_ms = timed(lambda r: mc.copy(flats[r % P].data_ptr(), flats[(r + 1) % P].data_ptr(), 4 * (N // 4) * 4, sh), reps)
 
-    step_bytes = (8 * P + 4 * (P + 5) + 8) * N
-    ru_bytes = 4 * (P + 5) * N
-    ru_avg = float(ru_ms.mean())
-    achieved = ru_bytes / ru_avg / 1e6
+    k_avg = float(k_ms.mean())
+    achieved = kernel_bytes / k_avg / 1e6
+    staged_bytes = (8 * P + 4 * (P + 5) + 8) * N
+    staged_ms, staged_k = (other_ms, other_k_ms) if fused else (ms_per_step, k_ms)
+    fused_ms, fused_k = (ms_per_step, k_ms) if fused else (other_ms, other_k_ms)
     out = {
         "metric": METRIC,
         "value": round(step_bytes / ms_per_step / 1e6, 1),
@@ -285,20 +333,28 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.n_tensors} tensors, N={N} fp32, P={P}, k={k}, "
                                f"lr={cfg.lr} mu={cfg.mu} wd={cfg.wd}, order={args.order}, "
                                f"{n_sets} rotating contribution sets",
-                   "step": f"{P} x mc_pack + mc_reduce_update (writes grad_out) + mc_unpack(weights)",
+                   "path": args.path,
+                   "step": ("mc_fused_step: contributions read from per-layer tensors, per-layer weights and "
+                            "momentum updated in place, flat grad_out written" if fused else
+                            f"{P} x mc_pack + mc_reduce_update (writes grad_out) + mc_unpack(weights)"),
                    "step_bytes": step_bytes},
         "pct_of_hbm_peak": round(100 * step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
-        "reduce_update": {"ms": round(ru_avg, 4), "ms_min": round(float(ru_ms.min()), 4),
-                          "ms_median": round(float(np.median(ru_ms)), 4),
-                          "GBps": round(achieved, 1),
-                          "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2)},
-        "pack": {"ms": round(pack_ms, 4), "GBps": round(8 * N / pack_ms / 1e6, 1)},
-        "unpack": {"ms": round(unpack_ms, 4), "GBps": round(8 * N / unpack_ms / 1e6, 1)},
+        "fused_step": {"ms_per_step": round(fused_ms, 4), "kernel_ms": round(float(fused_k.mean()), 4),
+                       "kernel_ms_min": round(float(fused_k.min()), 4),
+                       "GBps": round(kernel_bytes / float(fused_k.mean()) / 1e6, 1), "step_bytes": kernel_bytes},
+        "staged_step": {"ms_per_step": round(staged_ms, 4), "GBps": round(staged_bytes / staged_ms / 1e6, 1),
+                        "step_bytes": staged_bytes,
+                        "reduce_update_ms": round(float(staged_k.mean()), 4),
+                        "reduce_update_ms_min": round(float(staged_k.min()), 4),
+                        "reduce_update_GBps": round(kernel_bytes / float(staged_k.mean()) / 1e6, 1),
+                        "pack_ms": round(pack_ms, 4), "pack_GBps": round(8 * N / pack_ms / 1e6, 1),
+                        "unpack_ms": round(unpack_ms, 4), "unpack_GBps": round(8 * N / unpack_ms / 1e6, 1)},
         "copy_yardstick": {"ms": round(copy_ms, 4), "GBps": round(8 * (N // 4) * 4 / copy_ms / 1e6, 1)},
         "layout_create_ms": round(layout_ms, 3),
-        "roofline": {"bound": "hbm", "kernel": "reduce_update_kernel", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(cfg.name, P, k), "bytes_per_launch": ru_bytes},
+                     "traffic": measured_traffic(kernel_name, cfg.name, P, k), "bytes_per_launch": kernel_bytes,
+                     "kernel_ms": round(k_avg, 4)},
         "cpu_baseline": cpu,
         "parity_checked_first_step": cpu is not None,
         "library": os.path.relpath(mc.LIBRARY_PATH, ROOT),

@@ -162,6 +162,39 @@ int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32
                            void* grad_out, void* weights, void* momentum,
                            float lr, float mu, float wd, void* stream);
 
+/* ---- fused step: no staging of the contributions, no separate unpack --------------------
+ * Section 4.2's summing ranks add what arrived directly to "the local contributions from the
+ * GPUs"; nothing in the method requires a copy of each contribution into a flat buffer first.
+ * mc_fused_step computes exactly what  P x mc_pack + mc_reduce_update + mc_unpack  compute --
+ * same flat index space, same colour chunks, same per-colour sequence, same rounding -- but
+ * reads the contributions from their per-layer tensors, updates per-layer weights and momentum
+ * in place, and writes the reduced gradient as the flat payload.
+ *
+ * A tensor set is the device-resident list of one tensor pointer per layer of a layout
+ * (gradient tensors of one contribution, or the weights, or the momentum buffers).  Frameworks
+ * keep these tensors at fixed addresses, so a set is created once and reused every step.
+ *
+ * mc_tensor_set_create: tensors = host array of n_tensors device pointers (4-byte aligned;
+ *   entries of zero-length tensors are ignored).  Tensors of one set must not overlap each
+ *   other.  Uploads the list (one small allocation, one synchronous copy) and prepares the
+ *   layout on the current device.  The set refers to L: destroy it before L.
+ *   Errors: MC_ERR_INVALID_ARG, MC_ERR_ALIGN, MC_ERR_OVERLAP, MC_ERR_ALLOC, MC_ERR_HIP.
+ * mc_tensor_set_destroy: NULL is a no-op.
+ *
+ * mc_fused_step: contrib = host array of P sets (the same set may appear twice); order,
+ *   lr, mu, wd, stream and the arithmetic as in mc_reduce_update; grad_out = device N fp32 flat,
+ *   16-byte aligned, or NULL; weights, momentum = sets updated in place.  A tile whose operands
+ *   are not all 16-byte aligned relative to the payload falls back to narrower accesses, never
+ *   to different arithmetic.  Errors: MC_ERR_INVALID_ARG (NULL, P out of range, bad order row,
+ *   a set of another layout or device), MC_ERR_ALIGN, MC_ERR_OVERLAP (weights, momentum or
+ *   grad_out overlap each other or a contribution), MC_ERR_HIP. */
+typedef struct mc_tensor_set mc_tensor_set;   /* opaque */
+int mc_tensor_set_create(mc_layout* L, const void* const* tensors, mc_tensor_set** out);
+int mc_tensor_set_destroy(mc_tensor_set* S);
+int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                  void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                  float lr, float mu, float wd, void* stream);
+
 /* ---- diagnostics and tuning ---------------------------------------------------------- */
 /* Plain device-to-device copy of n_bytes (a multiple of 16; dst and src device, 16-byte
  * aligned, not overlapping) with the library's own 128-bit streaming kernel.  Not part of the
@@ -176,7 +209,8 @@ int mc_last_hip_error(void);           /* raw hipError_t of this thread's last M
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  * Returns MC_ERR_INVALID_ARG for an unknown option or a value outside its range. */
 enum {
-    MC_OPT_RU_UNROLL = 1,          /* 16-byte vectors per thread per tile in reduce_update: 1 or 2 */
+    MC_OPT_RU_UNROLL = 1,          /* 16-byte vectors per thread per tile in reduce_update and
+                                      fused_step: 1 or 2 */
     MC_OPT_RU_NONTEMPORAL = 2,     /* 0 / 1: streaming (non-temporal) loads of the contributions
                                       and store of grad_out.  Weights and momentum always use
                                       the normal policy so that they stay cached. */

@@ -1,0 +1,459 @@
+// Fused step: sum the P contributions straight out of their per-layer tensors, apply the SGD
+// update to per-layer weights and momentum in place, and emit the reduced gradient as the flat
+// colour-chunked payload -- no staging copy of any contribution, no separate unpack.
+//
+// The flat index space (and with it the colour chunks and each colour's summation sequence) is
+// exactly that of pack + reduce_update + unpack: element i of the payload is element
+// i - off[t] of tensor t.  A tensor set is the device-resident list of one tensor pointer per
+// layer.  Workgroups walk colour segments in tiles; a tile that lies inside one tensor with
+// every operand 16-byte aligned (almost all tiles of a CNN payload) resolves its P + 2 base
+// pointers once and then runs the same 128-bit streaming loop as reduce_update; any other tile
+// takes a per-vector path that looks tensors up as it goes.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "mc_internal.h"
+
+#pragma clang fp contract(off)
+
+struct mc_tensor_set {
+    const mc_layout* layout = nullptr;
+    int device = -1;
+    void** d_ptrs = nullptr;                            // device: n pointers
+    std::vector<const void*> ptrs;                      // host copy
+    std::vector<std::pair<uintptr_t, uintptr_t>> spans; // non-empty tensors' [begin, end), sorted
+};
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxSegs = 32;
+constexpr int kPtrSlots = 256;
+
+struct FusedArgs {
+    const float* const* x[kPtrSlots];   // x[s*np + q]: pointer table of the q-th term of segment s
+    int64_t lo[kMaxSegs];
+    int64_t hi[kMaxSegs];
+    int32_t first_block[kMaxSegs + 1];
+    int32_t n_segs;
+    float* const* w;                    // pointer tables of weights and momentum (per layer)
+    float* const* v;
+    float* g;                           // flat payload, may be null
+    const int64_t* off;                 // n+1 flat offsets
+    const int32_t* first_tensor;        // lookup: first tensor per kLookupElems flat elements
+    float lr, mu, wd;
+};
+
+template <bool NT>
+__device__ __forceinline__ float4 load4(const float* p) {
+    if (NT) {
+        float4 r;
+        r.x = __builtin_nontemporal_load(p + 0);
+        r.y = __builtin_nontemporal_load(p + 1);
+        r.z = __builtin_nontemporal_load(p + 2);
+        r.w = __builtin_nontemporal_load(p + 3);
+        return r;
+    }
+    return *reinterpret_cast<const float4*>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(float* p, const float4& q) {
+    if (NT) {
+        __builtin_nontemporal_store(q.x, p + 0);
+        __builtin_nontemporal_store(q.y, p + 1);
+        __builtin_nontemporal_store(q.z, p + 2);
+        __builtin_nontemporal_store(q.w, p + 3);
+    } else {
+        *reinterpret_cast<float4*>(p) = q;
+    }
+}
+
+// Each line is one rounding to binary32 (the file is compiled without contraction).
+__device__ __forceinline__ void sgd(float g, float& w, float& v, float lr, float mu, float wd) {
+    const float decay = wd * w;
+    const float d = g + decay;
+    const float mv = mu * v;
+    const float vn = mv + d;
+    const float step = lr * vn;
+    w = w - step;
+    v = vn;
+}
+
+__device__ __forceinline__ bool aligned16(const void* p) {
+    return (reinterpret_cast<uintptr_t>(p) & 15) == 0;
+}
+
+// P > 0: compile-time number of terms; P == 0: run-time count in Prt.
+template <int P, int U, bool HAS_G, bool NT>
+__global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int Prt) {
+    constexpr int64_t kTile = int64_t(kThreads) * 4 * U;
+    const int np = P > 0 ? P : Prt;
+
+    int s = 0;
+    while (s + 1 < a.n_segs && int(blockIdx.x) >= a.first_block[s + 1]) ++s;
+    const int64_t lo = a.lo[s];
+    const int64_t hi = a.hi[s];
+    const int64_t base = lo + int64_t(int(blockIdx.x) - a.first_block[s]) * kTile;  // multiple of 256
+    const int64_t end = base + kTile < hi ? base + kTile : hi;
+    const float* const* const* xs = a.x + s * np;
+
+    // The tensor holding the tile's first element (block-uniform).
+    int32_t t0 = a.first_tensor[base / mc::kLookupElems];
+    while (a.off[t0 + 1] <= base) ++t0;
+    const int64_t t0_begin = a.off[t0];
+    const int64_t t0_end = a.off[t0 + 1];
+
+    if (end - base == kTile && end <= t0_end) {
+        // Whole tile inside tensor t0: resolve the base pointers once.
+        const int64_t rel = base - t0_begin;
+        float* wp = a.w[t0] + rel;
+        float* vp = a.v[t0] + rel;
+        bool all_aligned = aligned16(wp) && aligned16(vp);
+        if (P > 0) {
+            const float* xp[P > 0 ? P : 1];
+#pragma unroll
+            for (int q = 0; q < P; ++q) {
+                xp[q] = xs[q][t0] + rel;
+                all_aligned = all_aligned && aligned16(xp[q]);
+            }
+            if (all_aligned) {
+                float4 t[P > 0 ? P : 1][U], wv[U], vv[U];
+                int64_t j[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) j[u] = (int64_t(u) * kThreads + threadIdx.x) * 4;
+#pragma unroll
+                for (int q = 0; q < P; ++q)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) t[q][u] = load4<NT>(xp[q] + j[u]);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
+                    vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    float4 acc = t[0][u];
+#pragma unroll
+                    for (int q = 1; q < P; ++q) {
+                        acc.x = acc.x + t[q][u].x;
+                        acc.y = acc.y + t[q][u].y;
+                        acc.z = acc.z + t[q][u].z;
+                        acc.w = acc.w + t[q][u].w;
+                    }
+                    if (HAS_G) store4<NT>(a.g + base + j[u], acc);
+                    sgd(acc.x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
+                    sgd(acc.y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
+                    sgd(acc.z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
+                    sgd(acc.w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
+                    *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
+                    *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
+                }
+                return;
+            }
+        } else {
+            for (int q = 0; q < np; ++q) all_aligned = all_aligned && aligned16(xs[q][t0] + rel);
+            if (all_aligned) {
+                float4 acc[U], wv[U], vv[U];
+                int64_t j[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    j[u] = (int64_t(u) * kThreads + threadIdx.x) * 4;
+                    wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
+                    vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
+                    acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
+                }
+                for (int q = 1; q < np; ++q) {
+                    const float* xq = xs[q][t0] + rel;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const float4 t = load4<NT>(xq + j[u]);
+                        acc[u].x = acc[u].x + t.x;
+                        acc[u].y = acc[u].y + t.y;
+                        acc[u].z = acc[u].z + t.z;
+                        acc[u].w = acc[u].w + t.w;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (HAS_G) store4<NT>(a.g + base + j[u], acc[u]);
+                    sgd(acc[u].x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
+                    sgd(acc[u].y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
+                    sgd(acc[u].z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
+                    sgd(acc[u].w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
+                    *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
+                    *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
+                }
+                return;
+            }
+        }
+    }
+
+    // General tile: tensor boundaries, the ragged end of the segment, or misaligned operands.
+    for (int u = 0; u < U; ++u) {
+        const int64_t i = base + (int64_t(u) * kThreads + threadIdx.x) * 4;
+        if (i >= end) break;
+        int32_t t = t0;
+        while (a.off[t + 1] <= i) ++t;  // ends: i < end <= N == off[n]
+        const int64_t rel = i - a.off[t];
+        bool vec = i + 4 <= end && i + 4 <= a.off[t + 1];
+        if (vec) {
+            vec = aligned16(a.w[t] + rel) && aligned16(a.v[t] + rel);
+            for (int q = 0; q < np && vec; ++q) vec = aligned16(xs[q][t] + rel);
+        }
+        if (vec) {
+            float4 acc = load4<NT>(xs[0][t] + rel);
+            for (int q = 1; q < np; ++q) {
+                const float4 x = load4<NT>(xs[q][t] + rel);
+                acc.x = acc.x + x.x;
+                acc.y = acc.y + x.y;
+                acc.z = acc.z + x.z;
+                acc.w = acc.w + x.w;
+            }
+            float* wp = a.w[t] + rel;
+            float* vp = a.v[t] + rel;
+            float4 wq = *reinterpret_cast<const float4*>(wp);
+            float4 vq = *reinterpret_cast<const float4*>(vp);
+            if (HAS_G) *reinterpret_cast<float4*>(a.g + i) = acc;
+            sgd(acc.x, wq.x, vq.x, a.lr, a.mu, a.wd);
+            sgd(acc.y, wq.y, vq.y, a.lr, a.mu, a.wd);
+            sgd(acc.z, wq.z, vq.z, a.lr, a.mu, a.wd);
+            sgd(acc.w, wq.w, vq.w, a.lr, a.mu, a.wd);
+            *reinterpret_cast<float4*>(wp) = wq;
+            *reinterpret_cast<float4*>(vp) = vq;
+        } else {
+            const int64_t stop = i + 4 < end ? i + 4 : end;
+            for (int64_t e = i; e < stop; ++e) {
+                while (a.off[t + 1] <= e) ++t;
+                const int64_t r = e - a.off[t];
+                float acc = xs[0][t][r];
+                for (int q = 1; q < np; ++q) acc = acc + xs[q][t][r];
+                float we = a.w[t][r], ve = a.v[t][r];
+                if (HAS_G) a.g[e] = acc;
+                sgd(acc, we, ve, a.lr, a.mu, a.wd);
+                a.w[t][r] = we;
+                a.v[t][r] = ve;
+            }
+        }
+    }
+}
+
+template <int P, int U>
+void launch_variant(bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
+    const dim3 grid(blocks), block(kThreads);
+#define MC_FUSED_LAUNCH(G, NT) hipLaunchKernelGGL((fused_step_kernel<P, U, G, NT>), grid, block, 0, s, a, Prt)
+    if (a.g) {
+        if (nt) MC_FUSED_LAUNCH(true, true); else MC_FUSED_LAUNCH(true, false);
+    } else {
+        if (nt) MC_FUSED_LAUNCH(false, true); else MC_FUSED_LAUNCH(false, false);
+    }
+#undef MC_FUSED_LAUNCH
+}
+
+template <int P>
+void launch_unroll(int unroll, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
+    if (unroll == 1)
+        launch_variant<P, 1>(nt, blocks, s, a, Prt);
+    else
+        launch_variant<P, 2>(nt, blocks, s, a, Prt);
+}
+
+void launch(int P, int unroll, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a) {
+    switch (P) {
+        case 1: launch_unroll<1>(unroll, nt, blocks, s, a, P); break;
+        case 2: launch_unroll<2>(unroll, nt, blocks, s, a, P); break;
+        case 3: launch_unroll<3>(unroll, nt, blocks, s, a, P); break;
+        case 4: launch_unroll<4>(unroll, nt, blocks, s, a, P); break;
+        case 5: launch_unroll<5>(unroll, nt, blocks, s, a, P); break;
+        case 6: launch_unroll<6>(unroll, nt, blocks, s, a, P); break;
+        case 7: launch_unroll<7>(unroll, nt, blocks, s, a, P); break;
+        case 8: launch_unroll<8>(unroll, nt, blocks, s, a, P); break;
+        default: launch_unroll<0>(unroll, nt, blocks, s, a, P); break;
+    }
+}
+
+// Do two sorted lists of [begin, end) spans intersect anywhere?
+bool spans_overlap(const std::vector<std::pair<uintptr_t, uintptr_t>>& A,
+                   const std::vector<std::pair<uintptr_t, uintptr_t>>& B) {
+    size_t i = 0, j = 0;
+    while (i < A.size() && j < B.size()) {
+        if (A[i].second <= B[j].first)
+            ++i;
+        else if (B[j].second <= A[i].first)
+            ++j;
+        else
+            return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mc_tensor_set_create(mc_layout* L, const void* const* tensors, mc_tensor_set** out) {
+    if (out) *out = nullptr;
+    if (!L || !tensors || !out) return MC_ERR_INVALID_ARG;
+    mc_tensor_set* S = new (std::nothrow) mc_tensor_set;
+    if (!S) return MC_ERR_ALLOC;
+    S->layout = L;
+    try {
+        S->ptrs.assign(tensors, tensors + L->n);
+        for (int32_t t = 0; t < L->n; ++t) {
+            const int64_t cnt = L->off[t + 1] - L->off[t];
+            if (cnt == 0) continue;
+            if (!tensors[t]) {
+                delete S;
+                return MC_ERR_INVALID_ARG;
+            }
+            if (!mc::aligned(tensors[t], 4)) {
+                delete S;
+                return MC_ERR_ALIGN;
+            }
+            const uintptr_t b = reinterpret_cast<uintptr_t>(tensors[t]);
+            S->spans.emplace_back(b, b + uintptr_t(cnt) * 4);
+        }
+        std::sort(S->spans.begin(), S->spans.end());
+        for (size_t i = 1; i < S->spans.size(); ++i) {
+            if (S->spans[i].first < S->spans[i - 1].second) {
+                delete S;
+                return MC_ERR_OVERLAP;
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        delete S;
+        return MC_ERR_ALLOC;
+    }
+    const mc::DeviceTables* dt = nullptr;
+    int rc = mc::device_tables(L, &dt);  // the kernels that read a set also read the layout's tables
+    if (rc == MC_OK) {
+        hipError_t e = hipGetDevice(&S->device);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&S->d_ptrs), size_t(L->n) * sizeof(void*));
+        if (e == hipSuccess)
+            e = hipMemcpy(S->d_ptrs, S->ptrs.data(), size_t(L->n) * sizeof(void*), hipMemcpyHostToDevice);
+        if (e != hipSuccess) rc = mc::hip_fail(e);
+    }
+    if (rc != MC_OK) {
+        if (S->d_ptrs) (void)hipFree(S->d_ptrs);
+        delete S;
+        return rc;
+    }
+    *out = S;
+    return MC_OK;
+}
+
+int mc_tensor_set_destroy(mc_tensor_set* S) {
+    if (!S) return MC_OK;
+    int rc = MC_OK;
+    if (S->d_ptrs) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e == hipSuccess && cur != S->device) e = hipSetDevice(S->device);
+        if (e == hipSuccess) e = hipFree(S->d_ptrs);
+        if (e != hipSuccess) rc = mc::hip_fail(e);
+        if (cur >= 0 && cur != S->device) (void)hipSetDevice(cur);
+    }
+    delete S;
+    return rc;
+}
+
+int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                  void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                  float lr, float mu, float wd, void* stream) {
+    if (!L || !contrib || !weights || !momentum || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if (weights->layout != L || momentum->layout != L) return MC_ERR_INVALID_ARG;
+    for (int32_t p = 0; p < P; ++p)
+        if (!contrib[p] || contrib[p]->layout != L) return MC_ERR_INVALID_ARG;
+    if (order) {
+        for (int32_t c = 0; c < L->k; ++c) {
+            uint64_t seen = 0;
+            for (int32_t q = 0; q < P; ++q) {
+                const int32_t o = order[size_t(c) * P + q];
+                if (o < 0 || o >= P || (seen >> o) & 1) return MC_ERR_INVALID_ARG;
+                seen |= uint64_t(1) << o;
+            }
+        }
+    }
+    if (L->N == 0) return MC_OK;
+    if (grad_out && !mc::aligned(grad_out, 16)) return MC_ERR_ALIGN;
+
+    // Nothing written (weights, momentum, grad_out) may overlap anything else of the call.
+    // A contribution may appear twice (it is only read).
+    const mc_tensor_set* written[2] = {weights, momentum};
+    if (spans_overlap(weights->spans, momentum->spans)) return MC_ERR_OVERLAP;
+    std::vector<std::pair<uintptr_t, uintptr_t>> gspan;
+    if (grad_out) {
+        const uintptr_t b = reinterpret_cast<uintptr_t>(grad_out);
+        gspan.emplace_back(b, b + uintptr_t(L->N) * 4);
+        for (const mc_tensor_set* wset : written)
+            if (spans_overlap(wset->spans, gspan)) return MC_ERR_OVERLAP;
+    }
+    for (int32_t p = 0; p < P; ++p) {
+        for (const mc_tensor_set* wset : written)
+            if (spans_overlap(contrib[p]->spans, wset->spans)) return MC_ERR_OVERLAP;
+        if (grad_out && spans_overlap(contrib[p]->spans, gspan)) return MC_ERR_OVERLAP;
+    }
+
+    const mc::DeviceTables* dt = nullptr;
+    const int rc = mc::device_tables(L, &dt);
+    if (rc != MC_OK) return rc;
+    int dev = -1;
+    MC_HIP_TRY(hipGetDevice(&dev));
+    if (weights->device != dev || momentum->device != dev) return MC_ERR_INVALID_ARG;
+    for (int32_t p = 0; p < P; ++p)
+        if (contrib[p]->device != dev) return MC_ERR_INVALID_ARG;
+
+    const int unroll = mc::option(MC_OPT_RU_UNROLL);
+    const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
+    const int64_t tile = int64_t(kThreads) * 4 * unroll;
+    const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / P);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    FusedArgs a;
+    a.w = reinterpret_cast<float* const*>(weights->d_ptrs);
+    a.v = reinterpret_cast<float* const*>(momentum->d_ptrs);
+    a.g = static_cast<float*>(grad_out);
+    a.off = dt->off;
+    a.first_tensor = dt->tile_first;
+    a.lr = lr;
+    a.mu = mu;
+    a.wd = wd;
+    int32_t c = 0;
+    while (c < L->k) {
+        int ns = 0;
+        int64_t blocks = 0;
+        a.first_block[0] = 0;
+        for (; c < L->k && ns < segs_per_launch; ++c) {
+            const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
+            if (hi == lo) continue;
+            const int64_t nblk = (hi - lo + tile - 1) / tile;
+            if (blocks + nblk > 0x7fffffff) {
+                if (ns == 0) return MC_ERR_INVALID_ARG;
+                break;
+            }
+            a.lo[ns] = lo;
+            a.hi[ns] = hi;
+            for (int32_t q = 0; q < P; ++q) {
+                const int32_t src = order ? order[size_t(c) * P + q] : q;
+                a.x[ns * P + q] = reinterpret_cast<const float* const*>(contrib[src]->d_ptrs);
+            }
+            blocks += nblk;
+            a.first_block[ns + 1] = int32_t(blocks);
+            ++ns;
+        }
+        if (ns == 0) break;
+        for (int i = ns * P; i < kPtrSlots; ++i) a.x[i] = nullptr;
+        for (int i = ns; i < kMaxSegs; ++i) {
+            a.lo[i] = a.hi[i] = 0;
+            a.first_block[i + 1] = a.first_block[ns];
+        }
+        a.n_segs = ns;
+        launch(P, unroll, nt, unsigned(blocks), s, a);
+        MC_HIP_TRY(hipGetLastError());
+    }
+    return MC_OK;
+}
+
+}  // extern "C"

@@ -16,6 +16,11 @@ namespace mc {
 #define MC_PACK_TILE_ELEMS 2048
 #endif
 constexpr int64_t kPackTileElems = MC_PACK_TILE_ELEMS;
+// Granularity of the "first tensor" lookup table: one entry per this many flat elements.  It is
+// the colour alignment, so every tile of every kernel (pack tiles, and reduce tiles, which
+// start at colour bounds) begins on an entry.
+constexpr int64_t kLookupElems = MC_COLOUR_ALIGN_ELEMS;
+static_assert(kPackTileElems % kLookupElems == 0, "pack tiles must start on lookup entries");
 // Device pointers that fit in one pack / unpack launch's kernel-argument block.
 constexpr int kPackMaxPtrs = 256;
 constexpr int kMaxDevices = 16;
@@ -23,7 +28,7 @@ constexpr int kMaxDevices = 16;
 struct DeviceTables {
     bool ready = false;
     int64_t* off = nullptr;         // n+1 flat offsets
-    int32_t* tile_first = nullptr;  // per pack tile: index of the first tensor that may intersect it
+    int32_t* tile_first = nullptr;  // per kLookupElems flat elements: first tensor that may intersect them
 };
 
 }  // namespace mc
@@ -34,7 +39,7 @@ struct mc_layout {
     int64_t N = 0;
     std::vector<int64_t> off;         // n+1
     std::vector<int64_t> bounds;      // k+1
-    std::vector<int32_t> tile_first;  // ceil(N / kPackTileElems) + 1
+    std::vector<int32_t> tile_first;  // ceil(N / kLookupElems) + 1
     std::mutex mu;                    // guards dev[] during prepare / destroy
     mc::DeviceTables dev[mc::kMaxDevices];
 };

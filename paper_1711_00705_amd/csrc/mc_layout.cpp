@@ -66,12 +66,13 @@ int mc_layout_create(const int64_t* numel, int32_t n_tensors, int32_t k_colours,
             L->bounds[c] = past_end ? total : int64_t(c) * C;
         }
 
-        // For each pack tile, the first tensor whose range ends after the tile's first element.
-        const int64_t tiles = (total + mc::kPackTileElems - 1) / mc::kPackTileElems;
+        // For each run of kLookupElems flat elements, the first tensor whose range ends after
+        // the run's first element.
+        const int64_t tiles = (total + mc::kLookupElems - 1) / mc::kLookupElems;
         L->tile_first.resize(size_t(tiles) + 1);
         int32_t t = 0;
         for (int64_t j = 0; j <= tiles; ++j) {
-            const int64_t first = j * mc::kPackTileElems;
+            const int64_t first = j * mc::kLookupElems;
             while (t < n_tensors && L->off[t + 1] <= first) ++t;
             L->tile_first[j] = t;  // == n_tensors only when first >= N
         }

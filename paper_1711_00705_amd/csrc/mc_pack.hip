@@ -59,8 +59,8 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
     const int64_t tile = tile0 + blockIdx.x;
     const int64_t lo = off[t0];
     const int64_t hi = off[t1];
-    const int32_t t_tile = max(tile_first[tile], t0);
     const int64_t tile_base = tile * mc::kPackTileElems;
+    const int32_t t_tile = max(tile_first[tile_base / mc::kLookupElems], t0);
 
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {

@@ -50,6 +50,10 @@ SIGNATURES = {
     "mc_reduce_update_roles": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
                                               ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp,
                                               ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_tensor_set_create": (ctypes.c_int, [_vp, _vpp, ctypes.POINTER(_vp)]),
+    "mc_tensor_set_destroy": (ctypes.c_int, [_vp]),
+    "mc_fused_step": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
+                                     ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
     "mc_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_int64, _vp]),
     "mc_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "mc_last_hip_error": (ctypes.c_int, []),
@@ -237,6 +241,63 @@ def rank_roles(n_nodes: int, k_colours: int, rank: int):
     _check(lib.mc_rank_roles(n_nodes, k_colours, rank, role.ctypes.data_as(_i32p),
                              cnt.ctypes.data_as(_i32p), ch.ctypes.data_as(_i32p)), "mc_rank_roles")
     return role, cnt, ch
+
+
+class TensorSet:
+    """Owns one ``mc_tensor_set*`` (keeps its layout alive)."""
+
+    def __init__(self, layout: Layout, tensor_ptrs):
+        if _count(tensor_ptrs) != layout.n:
+            raise ValueError("need one pointer per tensor of the layout")
+        self._layout = layout
+        self._h = _vp()
+        _check(lib.mc_tensor_set_create(layout.handle, _ptr_table(tensor_ptrs), ctypes.byref(self._h)),
+               "mc_tensor_set_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, _vp()
+            _check(lib.mc_tensor_set_destroy(h), "mc_tensor_set_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def tensor_set_create(layout: Layout, tensor_ptrs) -> TensorSet:
+    return TensorSet(layout, tensor_ptrs)
+
+
+def set_table(sets):
+    """A host array of tensor-set handles, reusable across calls."""
+    tab = (ctypes.c_void_p * max(len(sets), 1))()
+    for i, s in enumerate(sets):
+        tab[i] = s.handle if s is not None else None
+    tab.count = len(sets)
+    tab.keep = list(sets)
+    return tab
+
+
+def fused_step(layout: Layout, contrib_sets, order, grad_out_ptr: Optional[int], weights: TensorSet,
+               momentum: TensorSet, lr: float, mu: float, wd: float, stream: int = 0) -> None:
+    tab = contrib_sets if isinstance(contrib_sets, ctypes.Array) else set_table(contrib_sets)
+    P = tab.count
+    optr = None
+    if order is not None:
+        o = np.ascontiguousarray(order, dtype=np.int32)
+        if o.size != layout.k * P:
+            raise ValueError("order must hold k_colours * P entries")
+        optr = o.ctypes.data_as(_i32p)
+    _check(lib.mc_fused_step(layout.handle, tab, P, optr, grad_out_ptr,
+                             weights.handle if weights is not None else None,
+                             momentum.handle if momentum is not None else None,
+                             lr, mu, wd, stream or None), "mc_fused_step")
 
 
 def copy(dst_ptr: Optional[int], src_ptr: Optional[int], n_bytes: int, stream: int = 0) -> None:

@@ -156,3 +156,70 @@ class Step:
             assert len(gpu["layers"]) == len(ref["layers"])
             for t, (a, b) in enumerate(zip(gpu["layers"], ref["layers"])):
                 cmp(a, b, f"{what}: unpacked weights of tensor {t}")
+
+
+class FusedStep:
+    """mc_fused_step from host per-layer tensors, with the oracle's answer composed from its
+    pack, reduce_update and unpack."""
+
+    def __init__(self, sizes, k):
+        self.sizes = [int(s) for s in sizes]
+        self.L = mc.Layout(self.sizes, k)
+        self.O = oracle.Layout(self.sizes, k)
+
+    def run(self, contrib_tensors, w_tensors, v_tensors, lr, mu, wd, order=None, want_g=True,
+            misalign=None, misalign_w=None):
+        L, O = self.L, self.O
+        s = stream_handle()
+        placed = [place_tensors(ts, misalign) for ts in contrib_tensors]
+        w_dev, w_arena = place_tensors(w_tensors, misalign_w if misalign_w is not None else misalign)
+        v_dev, v_arena = place_tensors(v_tensors, misalign_w if misalign_w is not None else misalign)
+        sets = [mc.TensorSet(L, ptrs(d)) for d, _ in placed]
+        wset = mc.TensorSet(L, ptrs(w_dev))
+        vset = mc.TensorSet(L, ptrs(v_dev))
+        G = 64
+        gbuf = dev_empty(L.N + 2 * G) if want_g else None
+        g_ptr = gbuf[G:].data_ptr() if want_g else None
+        arenas_before = [a.cpu().numpy().view(np.uint32).copy() if a is not None else None
+                         for a in (w_arena, v_arena)]
+        mc.fused_step(L, sets, order, g_ptr if L.N else None, wset, vset, lr, mu, wd, s)
+        torch.cuda.synchronize()
+        N = L.N
+        gpu = dict(g=gbuf[G:G + N].cpu().numpy() if want_g else None,
+                   w_layers=[t.cpu().numpy() for t in w_dev], v_layers=[t.cpu().numpy() for t in v_dev])
+        if want_g:
+            h = gbuf.cpu().numpy().view(np.uint32)
+            assert np.all(h[:G] == 0xFFFFFFFF) and np.all(h[G + N:] == 0xFFFFFFFF), "g guard words overwritten"
+        # nothing outside the tensors of an arena may change
+        for arena, before, devs in ((w_arena, arenas_before[0], w_dev), (v_arena, arenas_before[1], v_dev)):
+            if arena is None:
+                continue
+            after = arena.cpu().numpy().view(np.uint32)
+            touched = np.zeros(after.size, bool)
+            for t in devs:
+                lo = (t.data_ptr() - arena.data_ptr()) // 4
+                touched[lo:lo + t.numel()] = True
+            assert np.array_equal(after[~touched], before[~touched]), "wrote outside the weight / momentum tensors"
+        # contributions are read-only
+        for (d, _), ts in zip(placed, contrib_tensors):
+            for a, b in zip(d, ts):
+                assert_bits(a.cpu().numpy(), b, "a contribution tensor changed")
+        for st in sets + [wset, vset]:
+            st.destroy()
+        # ---- oracle
+        xs = [oracle.pack(O, ts) for ts in contrib_tensors]
+        w = oracle.pack(O, w_tensors)
+        v = oracle.pack(O, v_tensors)
+        g = oracle.reduce_update(O, xs, w, v, lr, mu, wd, order=order, want_g=True)
+        ref = dict(g=g, w_layers=oracle.unpack(O, w), v_layers=oracle.unpack(O, v))
+        return gpu, ref
+
+    @staticmethod
+    def check(gpu, ref, what, nan_ok=False):
+        cmp = assert_bits_or_both_nan if nan_ok else assert_bits
+        if gpu["g"] is not None:
+            cmp(gpu["g"], ref["g"], f"{what}: reduced gradient")
+        for key in ("w_layers", "v_layers"):
+            assert len(gpu[key]) == len(ref[key])
+            for t, (a, b) in enumerate(zip(gpu[key], ref[key])):
+                cmp(a, b, f"{what}: {key}[{t}]")

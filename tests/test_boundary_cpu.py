@@ -22,7 +22,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
-    assert len(names) >= 18
+    assert len(names) >= 21
     raw = ctypes.CDLL(mc.LIBRARY_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in mc.h but not exported"
@@ -214,3 +214,19 @@ def test_one_hip_runtime_whatever_the_import_order(first):
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert out.returncode == 0, out.stderr
     assert out.stdout.split()[0] == "1", out.stdout
+
+
+def test_tensor_set_rejects_before_touching_the_gpu():
+    import ctypes
+    L = mc.Layout([1000, 0, 24], 2)
+    B = 0x10000000
+    out = ctypes.c_void_p(5)
+    f = mc.lib.mc_tensor_set_create
+    assert f(None, mc.ptr_table([B, None, B + 8192]), ctypes.byref(out)) == mc.ERR_INVALID_ARG and not out.value
+    assert f(L.handle, None, ctypes.byref(out)) == mc.ERR_INVALID_ARG
+    assert f(L.handle, mc.ptr_table([B, None, B + 8192]), None) == mc.ERR_INVALID_ARG
+    assert f(L.handle, mc.ptr_table([B, None, None]), ctypes.byref(out)) == mc.ERR_INVALID_ARG
+    assert f(L.handle, mc.ptr_table([B + 1, None, B + 8192]), ctypes.byref(out)) == mc.ERR_ALIGN
+    assert f(L.handle, mc.ptr_table([B, None, B + 3996]), ctypes.byref(out)) == mc.ERR_OVERLAP
+    assert mc.lib.mc_tensor_set_destroy(None) == mc.OK
+    assert mc.lib.mc_fused_step(L.handle, None, 1, None, None, None, None, 0., 0., 0., None) == mc.ERR_INVALID_ARG

@@ -1,0 +1,214 @@
+"""GPU parity of mc_fused_step (contributions read from per-layer tensors, per-layer weights
+and momentum updated in place, flat reduced gradient out) against the oracle's
+pack -> reduce_update -> unpack.  Bit-exact throughout."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle  # noqa: E402
+from paper_1711_00705_amd import mc  # noqa: E402
+from paper_1711_00705_amd import workloads as wl  # noqa: E402
+import gpu_harness as gh  # noqa: E402
+
+
+@pytest.fixture(autouse=True)
+def _restore_options():
+    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL)}
+    yield
+    for o, v in keep.items():
+        mc.set_option(o, v)
+    torch.cuda.synchronize()
+
+
+def _inputs(sizes, P, heavy=False, seed_v=5):
+    xs = [wl.contribution_tensors(sizes, p, heavy_tail=heavy) for p in range(P)]
+    w = wl.weight_tensors(sizes)
+    rng = np.random.Generator(np.random.PCG64(seed_v))
+    v = [rng.standard_normal(int(s), dtype=np.float32) * np.float32(0.01) for s in sizes]
+    return xs, w, v
+
+
+@pytest.mark.parametrize("order_kind", ["identity", "rotation"])
+@pytest.mark.parametrize("misalign", [None, [0], [1, 2, 3, 0]])
+def test_tiny_config(order_kind, misalign):
+    cfg = wl.workload("tiny")
+    order = None if order_kind == "identity" else wl.rotation_order(cfg.k, cfg.P)
+    st = gh.FusedStep(cfg.sizes, cfg.k)
+    xs, w, v = _inputs(cfg.sizes, cfg.P)
+    print(f"fused tiny order={order_kind} misalign={misalign}", flush=True)
+    gpu, ref = st.run(xs, w, v, cfg.lr, cfg.mu, cfg.wd, order=order, misalign=misalign)
+    st.check(gpu, ref, "fused tiny")
+
+
+# sizes that are multiples of four elements (like the CNN payloads): whole tiles inside one
+# tensor take the block-uniform path, tiles with tensor boundaries the per-vector path
+ALIGNED_SIZES = [64, 64, 36864, 64, 16384, 4096, 256, 256, 147456, 512, 8, 65536, 1000, 20]
+
+
+@pytest.mark.parametrize("unroll", [1, 2])
+@pytest.mark.parametrize("nt", [0, 1])
+@pytest.mark.parametrize("misalign", [None, [0, 0, 1, 0, 0, 2]])
+def test_cnn_like_layout(unroll, nt, misalign):
+    mc.set_option(mc.OPT_RU_UNROLL, unroll)
+    mc.set_option(mc.OPT_RU_NONTEMPORAL, nt)
+    k, P = 3, 4
+    st = gh.FusedStep(ALIGNED_SIZES, k)
+    xs, w, v = _inputs(ALIGNED_SIZES, P, heavy=True)
+    print(f"fused cnn-like unroll={unroll} nt={nt} misalign={misalign}", flush=True)
+    gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=wl.rotation_order(k, P), misalign=misalign)
+    st.check(gpu, ref, "fused cnn-like")
+    # weights / momentum misaligned differently from the contributions
+    gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=None, misalign=None, misalign_w=[0, 3])
+    st.check(gpu, ref, "fused cnn-like, misaligned weights")
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 6, 7, 8, 9, 16, 32])
+def test_every_contribution_count(P):
+    sizes = [5000, 4, 2048, 8192, 3]
+    k = 4
+    st = gh.FusedStep(sizes, k)
+    xs, w, v = _inputs(sizes, P)
+    print(f"fused P={P}", flush=True)
+    gpu, ref = st.run(xs, w, v, 0.05, 0.8, 1e-3, order=wl.random_order(k, P, seed=P), misalign=[0])
+    st.check(gpu, ref, f"fused P={P}")
+
+
+@pytest.mark.parametrize("sizes,k", [
+    ([1], 1), ([1], 5), ([3], 2), ([4], 1), ([255], 1), ([256], 2), ([257], 2), ([1023, 1], 3),
+    ([0, 5, 0, 0, 7], 2), ([1024], 1024), ([2000], 2003), ([777, 0, 1], 9), ([8192], 1),
+    ([8191], 1), ([8193], 1), ([100] * 50, 7), ([2048, 2048, 2048], 3), ([4096, 0, 4096], 1),
+])
+def test_edge_sizes(sizes, k):
+    st = gh.FusedStep(sizes, k)
+    P = 3
+    xs, w, v = _inputs(sizes, P)
+    print(f"fused edge sizes={sizes[:6]} k={k}", flush=True)
+    for mis in ([0], [3, 1]):
+        gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=wl.rotation_order(k, P), misalign=mis)
+        st.check(gpu, ref, f"fused sizes={sizes[:6]} k={k}")
+
+
+def test_many_colours_and_grad_out_null():
+    sizes = [40000, 20004]
+    k, P = 100, 8
+    st = gh.FusedStep(sizes, k)
+    xs, w, v = _inputs(sizes, P, heavy=True)
+    gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=wl.random_order(k, P, seed=9), misalign=[0])
+    st.check(gpu, ref, "fused k=100")
+    gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=None, want_g=False, misalign=[0])
+    assert gpu["g"] is None
+    st.check(gpu, ref, "fused grad_out=NULL")
+
+
+def test_flat_buffers_as_tensor_sets_and_repeated_contribution():
+    """A flat payload is the special case of a tensor set (pointers = flat + off[t]); the same
+    contribution may be passed twice (it is only read)."""
+    sizes = [3000, 500, 4096, 12]
+    k, P = 2, 3
+    L = mc.Layout(sizes, k)
+    O = oracle.Layout(sizes, k)
+    N = L.N
+    off = L.tensor_offsets()
+    rng = np.random.Generator(np.random.PCG64(4))
+    xs_h = [rng.standard_normal(N, dtype=np.float32) for _ in range(2)]
+    xs_h.append(xs_h[0])
+    w_h = rng.standard_normal(N, dtype=np.float32)
+    v_h = rng.standard_normal(N, dtype=np.float32)
+    xd = [gh.to_dev(xs_h[0]), gh.to_dev(xs_h[1])]
+    wd_, vd = gh.to_dev(w_h), gh.to_dev(v_h)
+
+    def as_set(t):
+        return mc.TensorSet(L, [t.data_ptr() + 4 * int(off[i]) for i in range(L.n)])
+    s0, s1, sw, sv = as_set(xd[0]), as_set(xd[1]), as_set(wd_), as_set(vd)
+    g = gh.dev_empty(N)
+    mc.fused_step(L, [s0, s1, s0], None, g.data_ptr(), sw, sv, 0.1, 0.9, 1e-4, gh.stream_handle())
+    torch.cuda.synchronize()
+    g_ref = oracle.reduce_update(O, xs_h, w_h, v_h, 0.1, 0.9, 1e-4)
+    gh.assert_bits(g.cpu().numpy(), g_ref, "g")
+    gh.assert_bits(wd_.cpu().numpy(), w_h, "w")
+    gh.assert_bits(vd.cpu().numpy(), v_h, "v")
+
+
+def test_fused_rejects_overlap_and_foreign_sets():
+    sizes = [1000, 24]
+    L = mc.Layout(sizes, 2)
+    L2 = mc.Layout(sizes, 2)
+    bufs = [gh.dev_empty(1024 + 24) for _ in range(4)]
+
+    def mk(layout, b):
+        return mc.TensorSet(layout, [b.data_ptr(), b[1024:].data_ptr()])
+    x, w, v = mk(L, bufs[0]), mk(L, bufs[1]), mk(L, bufs[2])
+    foreign = mk(L2, bufs[3])
+    g = gh.dev_empty(1024)
+
+    def code(*a):
+        try:
+            mc.fused_step(*a)
+        except mc.McError as e:
+            return e.code
+        return mc.OK
+    s = gh.stream_handle()
+    assert code(L, [x], None, g.data_ptr(), w, w, .1, .9, 0., s) == mc.ERR_OVERLAP
+    assert code(L, [w], None, g.data_ptr(), w, v, .1, .9, 0., s) == mc.ERR_OVERLAP
+    assert code(L, [x], None, bufs[0].data_ptr(), w, v, .1, .9, 0., s) == mc.ERR_OVERLAP
+    assert code(L, [x], None, bufs[1][4:].data_ptr(), w, v, .1, .9, 0., s) == mc.ERR_OVERLAP
+    assert code(L, [x], None, g[1:].data_ptr(), w, v, .1, .9, 0., s) == mc.ERR_ALIGN
+    assert code(L, [foreign], None, g.data_ptr(), w, v, .1, .9, 0., s) == mc.ERR_INVALID_ARG
+    assert code(L, [x], None, g.data_ptr(), foreign, v, .1, .9, 0., s) == mc.ERR_INVALID_ARG
+    assert code(L, [x], np.array([[0], [1]], np.int32), g.data_ptr(), w, v, .1, .9, 0., s) == mc.ERR_INVALID_ARG
+    with pytest.raises(mc.McError) as e:      # tensors of one set overlap each other
+        mc.TensorSet(L, [bufs[0].data_ptr(), bufs[0][500:].data_ptr()])
+    assert e.value.code == mc.ERR_OVERLAP
+    torch.cuda.synchronize()
+    # after all the rejected calls nothing was written
+    assert np.all(g.cpu().numpy().view(np.uint32) == 0xFFFFFFFF)
+
+
+@pytest.mark.parametrize("name,order_kind", [
+    ("resnet50", "rotation"), ("resnet50_heavy", "rotation"), ("vgg16", "identity"),
+])
+def test_full_size_fused(name, order_kind):
+    cfg = wl.workload(name)
+    print(f"fused full size {name} N={cfg.total} P={cfg.P} k={cfg.k}", flush=True)
+    order = None if order_kind == "identity" else wl.rotation_order(cfg.k, cfg.P)
+    st = gh.FusedStep(cfg.sizes, cfg.k)
+    xs = [wl.contribution_tensors(cfg.sizes, p, heavy_tail=cfg.heavy_tail) for p in range(cfg.P)]
+    gpu, ref = st.run(xs, wl.weight_tensors(cfg.sizes), wl.zero_tensors(cfg.sizes), cfg.lr, cfg.mu, cfg.wd,
+                      order=order)
+    st.check(gpu, ref, f"fused {name}")
+    torch.cuda.empty_cache()
+
+
+def test_googlenet_fused_steps_carry_state():
+    cfg = wl.workload("googlenet")
+    L = mc.Layout(cfg.sizes, cfg.k)
+    O = oracle.Layout(cfg.sizes, cfg.k)
+    N = L.N
+    order = wl.rotation_order(cfg.k, cfg.P)
+    s = gh.stream_handle()
+    w_layers, _ = gh.place_tensors(wl.weight_tensors(cfg.sizes))
+    v_layers, _ = gh.place_tensors(wl.zero_tensors(cfg.sizes))
+    wset, vset = mc.TensorSet(L, gh.ptrs(w_layers)), mc.TensorSet(L, gh.ptrs(v_layers))
+    g = gh.dev_empty(N)
+    wr = oracle.pack(O, wl.weight_tensors(cfg.sizes))
+    vr = np.zeros(N, np.float32)
+    steps = 20
+    for step in range(steps):
+        host = [wl.contribution_tensors(cfg.sizes, p, step=step) for p in range(cfg.P)]
+        dev = [gh.place_tensors(h)[0] for h in host]
+        sets = [mc.TensorSet(L, gh.ptrs(d)) for d in dev]
+        mc.fused_step(L, sets, order, g.data_ptr(), wset, vset, cfg.lr, cfg.mu, cfg.wd, s)
+        torch.cuda.synchronize()
+        for st in sets:
+            st.destroy()
+        gr = oracle.reduce_update(O, [oracle.pack(O, ts) for ts in host], wr, vr, cfg.lr, cfg.mu, cfg.wd, order=order)
+        if step + 1 in (1, 2, 10, steps):
+            print(f"googlenet fused step {step + 1}", flush=True)
+            gh.assert_bits(g.cpu().numpy(), gr, f"g after step {step + 1}")
+            for a, b in zip(w_layers, oracle.unpack(O, wr)):
+                gh.assert_bits(a.cpu().numpy(), b, f"w after step {step + 1}")
+            for a, b in zip(v_layers, oracle.unpack(O, vr)):
+                gh.assert_bits(a.cpu().numpy(), b, f"v after step {step + 1}")
