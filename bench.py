@@ -60,6 +60,8 @@ def parse():
                     help="fused: one mc_fused_step per step; staged: P packs + reduce_update + unpack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--pipeline-packets", type=int, default=0,
+                    help="also run the packet-pipelined experiment with this many packets per colour")
     ap.add_argument("--kernel-only", action="store_true",
                     help="time only mc_reduce_update launches (for profiler runs)")
     return ap.parse_args()
@@ -134,6 +136,88 @@ def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, step
                      "sample": f"{n2} whole steps, one host thread per colour ({nthr}) / per pack ({cfg.P})"},
         "host_cpus": ncpu,
     }
+
+
+def pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, stream, packets, reps):
+    """Section 4.2 pipelines the reductions packet by packet.  Here half of the P contributions
+    are resident and the other half "arrive": staging copies on a second stream stand in for
+    network buffers landing in the receive buffers.  Unpipelined: all copies, then one
+    mc_reduce_update.  Pipelined: per packet (colours interleaved, as the colours progress
+    concurrently), copy the packet of every arriving contribution, then mc_reduce_update_range
+    on it as soon as its copies are done.  On one GPU copies and sum share the same HBM, so
+    this measures latency hiding, not extra bandwidth."""
+    N, P, k = cfg.total, cfg.P, cfg.k
+    arriving = list(range(P // 2, P))
+    src = [torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3 for _ in arriving]
+    copy_stream = torch.cuda.Stream()
+    sh = int(stream.cuda_stream)
+    bounds = [int(b) for b in L.colour_bounds()]
+    pk = []
+    for c in range(k):
+        lo, hi = bounds[c], bounds[c + 1]
+        if hi == lo:
+            continue
+        step = -(-(hi - lo) // packets)
+        step = -(-step // 256) * 256
+        pk.append([(b, min(hi, b + step)) for b in range(lo, hi, step)])
+    order_of_packets = [p[j] for j in range(max(len(p) for p in pk)) for p in pk if j < len(p)]
+
+    def pipelined(main=None):
+        main = main or stream
+        mh = int(main.cuda_stream)
+        copy_stream.wait_stream(main)
+        for (b, e) in order_of_packets:
+            with torch.cuda.stream(copy_stream):
+                for q, s_ in zip(arriving, src):
+                    mc.copy(flats[q].data_ptr() + 4 * b, s_.data_ptr() + 4 * b, 4 * (e - b), int(copy_stream.cuda_stream))
+                ev = torch.cuda.Event()
+                ev.record(copy_stream)
+            main.wait_event(ev)
+            mc.reduce_update_range(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                                   cfg.lr, cfg.mu, cfg.wd, b, e, mh)
+        main.wait_stream(copy_stream)
+
+    def unpipelined_own_copy(main=None):
+        main = main or stream
+        copy_stream.wait_stream(main)
+        with torch.cuda.stream(copy_stream):
+            for q, s_ in zip(arriving, src):
+                mc.copy(flats[q].data_ptr(), s_.data_ptr(), 4 * (N // 4) * 4, int(copy_stream.cuda_stream))
+        main.wait_stream(copy_stream)
+        mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                         cfg.lr, cfg.mu, cfg.wd, int(main.cuda_stream))
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def captured(fn):
+        """The same sequence captured once into a HIP graph (kernel nodes and event edges only)
+        and replayed: removes the per-packet host cost of issuing launches and event waits."""
+        cap = torch.cuda.Stream()
+        cap.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=cap):
+            fn(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        return timed(graph.replay)
+
+    out = {"packets_per_colour": packets, "n_packets": len(order_of_packets),
+           "arriving_contributions": len(arriving),
+           "unpipelined_ms": round(timed(unpipelined_own_copy), 4),
+           "pipelined_ms": round(timed(pipelined), 4)}
+    out["unpipelined_graph_ms"] = round(captured(unpipelined_own_copy), 4)
+    out["pipelined_graph_ms"] = round(captured(pipelined), 4)
+    return out
 
 
 def main():
@@ -323,6 +407,11 @@ def main():
     unpack_ms = timed(lambda r: mc.unpack(L, w.data_ptr(), w_table, sh), reps)
     copy_ms = timed(lambda r: mc.copy(flats[r % P].data_ptr(), flats[(r + 1) % P].data_ptr(), 4 * (N // 4) * 4, sh), reps)
 
+    pipelined = None
+    if args.pipeline_packets > 0:
+        pipelined = pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, stream,
+                                        args.pipeline_packets, reps=max(5, min(args.steps, 30)))
+
     k_avg = float(k_ms.mean())
     achieved = kernel_bytes / k_avg / 1e6
     staged_bytes = (8 * P + 4 * (P + 5) + 8) * N
@@ -365,6 +454,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(kernel_name, cfg.name, P, k), "bytes_per_launch": kernel_bytes,
                      "kernel_ms": round(k_avg, 4)},
+        "pipelined_packets": pipelined,
         "cpu_baseline": cpu,
         "parity_checked_first_step": cpu is not None,
         "library": os.path.relpath(mc.LIBRARY_PATH, ROOT),

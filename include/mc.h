@@ -162,6 +162,26 @@ int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32
                            void* grad_out, void* weights, void* momentum,
                            float lr, float mu, float wd, void* stream);
 
+/* ---- packets: the reduction restricted to a sub-range of the payload -------------------
+ * Section 4.2: the k reductions are pipelined -- network packets of every colour move
+ * concurrently and a summing rank adds each packet as it arrives rather than waiting for whole
+ * chunks.  The per-packet operation is mc_reduce_update (or its roles form) restricted to the
+ * flat elements [elem_begin, elem_end): every colour is cut to that range, everything outside is
+ * neither read nor written.  Because the step is elementwise, running any partition of [0, N)
+ * into packets, in any order and on any streams, gives bit for bit the result of the whole call.
+ * The caller sequences packets against their arrival (e.g. an event wait on `stream` before
+ * the call).
+ *
+ * elem_begin, elem_end: 0 <= begin <= end <= N, begin a multiple of MC_COLOUR_ALIGN_ELEMS, end a
+ *   multiple of it or equal to N; otherwise MC_ERR_INVALID_ARG.  An empty range is a no-op.
+ * n_terms, do_update: both NULL (every colour adds all P terms and updates) or both given, as in
+ *   mc_reduce_update_roles.  Everything else as mc_reduce_update. */
+int mc_reduce_update_range(const mc_layout* L, const void* const* contrib, int32_t P,
+                           const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
+                           void* grad_out, void* weights, void* momentum,
+                           float lr, float mu, float wd,
+                           int64_t elem_begin, int64_t elem_end, void* stream);
+
 /* ---- fused step: no staging of the contributions, no separate unpack --------------------
  * Section 4.2's summing ranks add what arrived directly to "the local contributions from the
  * GPUs"; nothing in the method requires a copy of each contribution into a flat buffer first.

@@ -194,3 +194,20 @@ def reduce_update_roles(layout: Layout, contrib: Sequence[np.ndarray], n_terms, 
         ctypes.c_float(lr), ctypes.c_float(mu), ctypes.c_float(wd))
     if rc != 0:
         raise ValueError("mco_reduce_update_roles: invalid argument")
+
+
+def reduce_update_range(layout: Layout, contrib: Sequence[np.ndarray], g, w, v,
+                        lr: float, mu: float, wd: float, begin: int, end: int, order=None) -> None:
+    """The step restricted to flat elements [begin, end) (one packet of the pipelined
+    reduction, Section 4.2): every colour is cut to that range; g, w, v are changed IN PLACE
+    there and nowhere else."""
+    P = len(contrib)
+    for c in range(layout.k):
+        lo = max(int(layout.bounds[c]), begin)
+        hi = min(int(layout.bounds[c + 1]), end)
+        if hi <= lo:
+            continue
+        seq = np.arange(P, dtype=np.int32) if order is None else np.ascontiguousarray(order[c], dtype=np.int32)
+        _load().mco_reduce_update_colour(lo, hi, _ptr_table(contrib), P, _ptr(seq, ctypes.c_int32),
+                                         None if g is None else g.ctypes.data, w.ctypes.data, v.ctypes.data,
+                                         ctypes.c_float(lr), ctypes.c_float(mu), ctypes.c_float(wd))

@@ -239,10 +239,17 @@ void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_
 
 // Shared by both entry points.  n_terms / do_update are null for the uniform call (every
 // colour adds all P terms and updates).
+//
+// [r_lo, r_hi) restricts the call to a sub-range of the payload (a packet): every colour is
+// intersected with it.  r_lo and r_hi are multiples of the colour alignment (r_hi may also be
+// N), so every segment still starts on a 16-byte boundary.
 int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
         const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
-        void* momentum, float lr, float mu, float wd, void* stream) {
+        void* momentum, float lr, float mu, float wd, int64_t r_lo, int64_t r_hi, void* stream) {
     if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if (r_lo < 0 || r_hi < r_lo || r_hi > L->N) return MC_ERR_INVALID_ARG;
+    if (r_lo % MC_COLOUR_ALIGN_ELEMS != 0) return MC_ERR_INVALID_ARG;
+    if (r_hi % MC_COLOUR_ALIGN_ELEMS != 0 && r_hi != L->N) return MC_ERR_INVALID_ARG;
     if ((n_terms == nullptr) != (do_update == nullptr)) return MC_ERR_INVALID_ARG;
     if (order) {
         for (int32_t c = 0; c < L->k; ++c) {
@@ -254,15 +261,16 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
             }
         }
     }
-    bool any_update = n_terms == nullptr, any_sum_only = false;
-    if (n_terms) {
-        for (int32_t c = 0; c < L->k; ++c) {
-            if (n_terms[c] < 0 || n_terms[c] > P) return MC_ERR_INVALID_ARG;
-            if (n_terms[c] == 0 || L->bounds[c + 1] == L->bounds[c]) continue;
-            if (do_update[c]) any_update = true; else any_sum_only = true;
-        }
+    // What colour c contributes to this call: its range cut to [r_lo, r_hi).
+    auto seg_lo = [&](int32_t c) { return std::max(L->bounds[c], r_lo); };
+    auto seg_hi = [&](int32_t c) { return std::max(seg_lo(c), std::min(L->bounds[c + 1], r_hi)); };
+    bool any_update = false, any_sum_only = false;
+    for (int32_t c = 0; c < L->k; ++c) {
+        if (n_terms && (n_terms[c] < 0 || n_terms[c] > P)) return MC_ERR_INVALID_ARG;
+        if ((n_terms && n_terms[c] == 0) || seg_hi(c) == seg_lo(c)) continue;
+        if (!do_update || do_update[c]) any_update = true; else any_sum_only = true;
     }
-    if (L->N == 0) return MC_OK;
+    if (!any_update && !any_sum_only) return MC_OK;  // nothing in range
     if (any_update && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
     if (any_sum_only && !grad_out) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
@@ -303,7 +311,7 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
         if (done[c0]) continue;
         const int32_t cnt = n_terms ? n_terms[c0] : P;
         const bool upd = do_update ? do_update[c0] != 0 : true;
-        if (cnt == 0 || L->bounds[c0 + 1] == L->bounds[c0]) {
+        if (cnt == 0 || seg_hi(c0) == seg_lo(c0)) {
             done[c0] = 1;
             continue;
         }
@@ -315,7 +323,7 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
             a.first_block[0] = 0;
             for (; c < L->k && ns < segs_per_launch; ++c) {
                 if (done[c]) continue;
-                const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
+                const int64_t lo = seg_lo(c), hi = seg_hi(c);
                 const int32_t cc = n_terms ? n_terms[c] : P;
                 const bool cu = do_update ? do_update[c] != 0 : true;
                 if (cc == 0 || hi == lo) {
@@ -360,15 +368,25 @@ extern "C" {
 int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
                      void* grad_out, void* weights, void* momentum, float lr, float mu, float wd,
                      void* stream) {
-    return run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, lr, mu, wd, stream);
+    if (!L) return MC_ERR_INVALID_ARG;
+    return run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, lr, mu, wd, 0, L->N, stream);
 }
 
 int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32_t P,
                            const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
                            void* grad_out, void* weights, void* momentum, float lr, float mu,
                            float wd, void* stream) {
-    if (!n_terms || !do_update) return MC_ERR_INVALID_ARG;
-    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, lr, mu, wd, stream);
+    if (!L || !n_terms || !do_update) return MC_ERR_INVALID_ARG;
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, lr, mu, wd, 0, L->N, stream);
+}
+
+int mc_reduce_update_range(const mc_layout* L, const void* const* contrib, int32_t P,
+                           const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
+                           void* grad_out, void* weights, void* momentum, float lr, float mu,
+                           float wd, int64_t elem_begin, int64_t elem_end, void* stream) {
+    if (!L) return MC_ERR_INVALID_ARG;
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, lr, mu, wd,
+               elem_begin, elem_end, stream);
 }
 
 }  // extern "C"

@@ -50,6 +50,10 @@ SIGNATURES = {
     "mc_reduce_update_roles": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
                                               ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp,
                                               ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_reduce_update_range": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
+                                              ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp,
+                                              ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                              ctypes.c_int64, ctypes.c_int64, _vp]),
     "mc_tensor_set_create": (ctypes.c_int, [_vp, _vpp, ctypes.POINTER(_vp)]),
     "mc_tensor_set_destroy": (ctypes.c_int, [_vp]),
     "mc_fused_step": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
@@ -223,6 +227,29 @@ def reduce_update_roles(layout: Layout, contrib_ptrs, order, n_terms, do_update,
                                       du.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
                                       grad_out_ptr, weights_ptr, momentum_ptr, lr, mu, wd,
                                       stream or None), "mc_reduce_update_roles")
+
+
+def reduce_update_range(layout: Layout, contrib_ptrs, order, grad_out_ptr: Optional[int],
+                        weights_ptr: Optional[int], momentum_ptr: Optional[int],
+                        lr: float, mu: float, wd: float, elem_begin: int, elem_end: int,
+                        stream: int = 0, n_terms=None, do_update=None) -> None:
+    P = _count(contrib_ptrs)
+    optr = None
+    if order is not None:
+        o = np.ascontiguousarray(order, dtype=np.int32)
+        if o.size != layout.k * P:
+            raise ValueError("order must hold k_colours * P entries")
+        optr = o.ctypes.data_as(_i32p)
+    ntp = dup = None
+    if n_terms is not None or do_update is not None:
+        nt = np.ascontiguousarray(n_terms, dtype=np.int32)
+        du = np.ascontiguousarray(do_update, dtype=np.uint8)
+        if nt.size != layout.k or du.size != layout.k:
+            raise ValueError("n_terms and do_update must hold k_colours entries")
+        ntp, dup = nt.ctypes.data_as(_i32p), du.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    _check(lib.mc_reduce_update_range(layout.handle, _ptr_table(contrib_ptrs), P, optr, ntp, dup,
+                                      grad_out_ptr, weights_ptr, momentum_ptr, lr, mu, wd,
+                                      elem_begin, elem_end, stream or None), "mc_reduce_update_range")
 
 
 def colour_trees(n_nodes: int, k_colours: int) -> np.ndarray:

@@ -22,7 +22,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
-    assert len(names) >= 21
+    assert len(names) >= 22
     raw = ctypes.CDLL(mc.LIBRARY_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in mc.h but not exported"
@@ -230,3 +230,21 @@ def test_tensor_set_rejects_before_touching_the_gpu():
     assert f(L.handle, mc.ptr_table([B, None, B + 3996]), ctypes.byref(out)) == mc.ERR_OVERLAP
     assert mc.lib.mc_tensor_set_destroy(None) == mc.OK
     assert mc.lib.mc_fused_step(L.handle, None, 1, None, None, None, None, 0., 0., 0., None) == mc.ERR_INVALID_ARG
+
+
+def test_reduce_update_range_rejects_before_launch():
+    L = mc.Layout([1000, 24], 2)          # N = 1024, bounds 0, 512, 1024
+    B = 0x10000000
+    x = [B + (i << 20) for i in range(2)]
+    g, w, v = B + (8 << 20), B + (9 << 20), B + (10 << 20)
+    rr = mc.reduce_update_range
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., -256, 512) == mc.ERR_INVALID_ARG
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 512, 256) == mc.ERR_INVALID_ARG
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 0, 1025) == mc.ERR_INVALID_ARG
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 100, 512) == mc.ERR_INVALID_ARG     # begin unaligned
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 0, 700) == mc.ERR_INVALID_ARG       # end unaligned, not N
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 256, 256) == mc.OK                  # empty packet
+    assert _code(rr, L, x, None, g, w + 4, v, .1, .9, 0., 0, 256) == mc.ERR_ALIGN
+    assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 0, 256, 0, [2, 3], [1, 1]) == mc.ERR_INVALID_ARG  # n_terms > P
+    L2 = mc.Layout([1000], 1)             # N = 1000: a range may end at N
+    assert _code(rr, L2, x, None, g, w, v, .1, .9, 0., 768, 1000, 0) in (mc.OK, mc.ERR_HIP)

@@ -88,3 +88,32 @@ def test_roles_leave_skipped_colours_alone_and_match_uniform_call():
         ref_w, ref_v = (w2, v2) if updated else (w0, v0)
         pins.assert_bits_equal(w[lo:hi], ref_w[lo:hi], "w range")
         pins.assert_bits_equal(v[lo:hi], ref_v[lo:hi], "v range")
+
+
+def test_oracle_range_partition_equals_whole_call():
+    sizes = [3000, 77, 1200]
+    k, P = 3, 4
+    L = oracle.Layout(sizes, k)
+    N = L.N
+    rng = np.random.Generator(np.random.PCG64(9))
+    xs = [rng.standard_normal(N, dtype=np.float32) for _ in range(P)]
+    w0 = rng.standard_normal(N, dtype=np.float32)
+    v0 = rng.standard_normal(N, dtype=np.float32)
+    order = np.array([[1, 0, 3, 2], [3, 2, 1, 0], [0, 1, 2, 3]], np.int32)
+    w1, v1 = w0.copy(), v0.copy()
+    g1 = oracle.reduce_update(L, xs, w1, v1, 0.1, 0.9, 1e-3, order=order)
+    for packet in (256, 768, 5000):
+        g2, w2, v2 = np.zeros(N, np.float32), w0.copy(), v0.copy()
+        cuts = list(range(0, N, packet)) + [N]
+        for b, e in reversed(list(zip(cuts[:-1], cuts[1:]))):
+            oracle.reduce_update_range(L, xs, g2, w2, v2, 0.1, 0.9, 1e-3, b, e, order=order)
+        pins.assert_bits_equal(g2, g1, "g")
+        pins.assert_bits_equal(w2, w1, "w")
+        pins.assert_bits_equal(v2, v1, "v")
+    # one packet leaves everything else alone
+    g3, w3, v3 = np.full(N, 5.0, np.float32), w0.copy(), v0.copy()
+    oracle.reduce_update_range(L, xs, g3, w3, v3, 0.1, 0.9, 1e-3, 1024, 2048, order=order)
+    out = np.ones(N, bool)
+    out[1024:2048] = False
+    assert np.all(g3[out] == 5.0) and np.array_equal(w3[out], w0[out]) and np.array_equal(v3[out], v0[out])
+    pins.assert_bits_equal(g3[1024:2048], g1[1024:2048], "packet g")
