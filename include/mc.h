@@ -215,6 +215,49 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
                   void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
                   float lr, float mu, float wd, void* stream);
 
+/* ---- variants of the update: run-time hyper-parameters, Nesterov, the LR schedule ---------
+ * Section 5 ("Experimental setup"): the learning rate starts at 0.1, is ramped linearly to
+ * 0.1*k*n/256 (k = batch per GPU, n = number of workers), and is divided by 10 after every 30
+ * epochs of a 90-epoch run.  The rate therefore changes from step to step, while a step captured
+ * into a HIP graph replays fixed kernel arguments: the `_ex` entry points can read {lr, mu, wd}
+ * from device memory when the kernel runs.
+ *
+ * mc_update_spec: lr, mu, wd are used when hyper_dev is NULL; otherwise hyper_dev points to three
+ *   device floats {lr, mu, wd} (4-byte aligned) read by the kernel.  nesterov = 0 is the update of
+ *   mc_reduce_update; nesterov = 1 applies the look-ahead form  w' = w - lr*(d + mu*v')  with the
+ *   same d and v' (the paper names no variant; the Torch ResNet recipe it builds on uses this
+ *   one).  Any other value: MC_ERR_INVALID_ARG.
+ * mc_reduce_update_ex: the most general form of mc_reduce_update: n_terms / do_update both NULL or
+ *   both given (as in _roles), range as in _range with elem_end < 0 meaning N.
+ * mc_fused_step_ex: mc_fused_step with a spec.
+ * mc_hyper_write: enqueues on `stream` a write of {lr, mu, wd} to hyper_dev (a one-thread kernel;
+ *   no host memory is read after the call returns, nothing synchronises). */
+typedef struct mc_update_spec {
+    float lr, mu, wd;
+    const float* hyper_dev;
+    int32_t nesterov;
+} mc_update_spec;
+int mc_reduce_update_ex(const mc_layout* L, const void* const* contrib, int32_t P,
+                        const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
+                        void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
+                        int64_t elem_begin, int64_t elem_end, void* stream);
+int mc_fused_step_ex(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const mc_update_spec* spec, void* stream);
+int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream);
+
+/* The schedule of Section 5 as a function of the position in training, in epochs (fractions
+ * allowed): with target = base_lr * batch_per_gpu * n_workers / 256,
+ *   epoch <  warmup_epochs:  base_lr + (target - base_lr) * epoch / warmup_epochs
+ *   epoch >= warmup_epochs:  target / 10^floor(epoch / drop_every_epochs)
+ * The paper gives base_lr = 0.1, drop_every_epochs = 30 and a 90-epoch run; it does not say how
+ * long the ramp lasts (the schedule it cites ramps over 5 epochs), so that is an argument.
+ * Host-only.  Writes the rate to *lr_out.  Errors: MC_ERR_INVALID_ARG (NULL, base_lr not finite
+ * or <= 0, batch_per_gpu < 1, n_workers < 1, warmup_epochs < 0, drop_every_epochs <= 0,
+ * epoch < 0 or not finite). */
+int mc_lr_schedule(float base_lr, int32_t batch_per_gpu, int32_t n_workers, float warmup_epochs,
+                   float drop_every_epochs, float epoch, float* lr_out);
+
 /* ---- diagnostics and tuning ---------------------------------------------------------- */
 /* Plain device-to-device copy of n_bytes (a multiple of 16; dst and src device, 16-byte
  * aligned, not overlapping) with the library's own 128-bit streaming kernel.  Not part of the

@@ -49,6 +49,8 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_float, ctypes.c_float, ctypes.c_float]
         lib.mco_reduce_update_colour.restype = None
+        lib.mco_reduce_update_colour_nesterov.argtypes = lib.mco_reduce_update_colour.argtypes
+        lib.mco_reduce_update_colour_nesterov.restype = None
         lib.mco_reduce_update.argtypes = [
             i64p, ctypes.c_int32, vpp, ctypes.c_int32, i32p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -211,3 +213,22 @@ def reduce_update_range(layout: Layout, contrib: Sequence[np.ndarray], g, w, v,
         _load().mco_reduce_update_colour(lo, hi, _ptr_table(contrib), P, _ptr(seq, ctypes.c_int32),
                                          None if g is None else g.ctypes.data, w.ctypes.data, v.ctypes.data,
                                          ctypes.c_float(lr), ctypes.c_float(mu), ctypes.c_float(wd))
+
+
+def reduce_update_nesterov(layout: Layout, contrib: Sequence[np.ndarray], w: np.ndarray, v: np.ndarray,
+                           lr: float, mu: float, wd: float, order=None) -> np.ndarray:
+    """reduce_update with the Nesterov look-ahead step; w and v IN PLACE, returns g."""
+    P = len(contrib)
+    for p, a in enumerate(contrib):
+        _check_f32(a, layout.N, f"contrib {p}")
+    _check_f32(w, layout.N, "w")
+    _check_f32(v, layout.N, "v")
+    o, _ = _order_arg(order, layout.k, P)
+    g = np.empty(layout.N, dtype=np.float32)
+    for c in range(layout.k):
+        seq = np.arange(P, dtype=np.int32) if o is None else np.ascontiguousarray(o[c])
+        _load().mco_reduce_update_colour_nesterov(
+            int(layout.bounds[c]), int(layout.bounds[c + 1]), _ptr_table(contrib), P,
+            _ptr(seq, ctypes.c_int32), g.ctypes.data, w.ctypes.data, v.ctypes.data,
+            ctypes.c_float(lr), ctypes.c_float(mu), ctypes.c_float(wd))
+    return g

@@ -92,6 +92,31 @@ void mco_reduce_update_colour(int64_t lo, int64_t hi, const float *const *x, int
     }
 }
 
+/* The same with the Nesterov look-ahead step (the paper names no variant of "SGD"; the Torch
+ * ResNet recipe it builds on uses this one): d and v' as above, then
+ *   w' = w - lr * (d + mu * v')
+ * again with every operation rounded separately. */
+void mco_reduce_update_colour_nesterov(int64_t lo, int64_t hi, const float *const *x, int32_t P,
+                                       const int32_t *seq, float *g, float *w, float *v,
+                                       float lr, float mu, float wd)
+{
+    for (int64_t i = lo; i < hi; ++i) {
+        float acc = x[seq[0]][i];
+        for (int32_t q = 1; q < P; ++q)
+            acc = acc + x[seq[q]][i];
+        if (g) g[i] = acc;
+        const float decay = wd * w[i];
+        const float d = acc + decay;
+        const float mv = mu * v[i];
+        const float vn = mv + d;
+        const float look = mu * vn;
+        const float dir = d + look;
+        const float step = lr * dir;
+        w[i] = w[i] - step;
+        v[i] = vn;
+    }
+}
+
 /* One colour, sum only: what a leaf or inner node of the colour's tree produces (its partial
  * sum, handed to the parent).  The SGD step needs the complete sum, which only the root has
  * (Section 4.2: roots and non-leaf nodes sum, leaves only send; the result is broadcast from

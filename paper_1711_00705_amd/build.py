@@ -8,7 +8,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmc.so")
-SOURCES = ("mc_layout.cpp", "mc_pack.hip", "mc_reduce_update.hip", "mc_fused.hip", "mc_copy.hip", "mc_trees.cpp")
+SOURCES = ("mc_layout.cpp", "mc_pack.hip", "mc_reduce_update.hip", "mc_fused.hip", "mc_schedule.hip", "mc_copy.hip",
+           "mc_trees.cpp")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # every add / multiply of the update is rounded on its own: no fused multiply-add

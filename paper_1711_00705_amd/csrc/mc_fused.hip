@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "mc_internal.h"
+#include "mc_update.h"
 
 #pragma clang fp contract(off)
 
@@ -43,7 +44,7 @@ struct FusedArgs {
     float* g;                           // flat payload, may be null
     const int64_t* off;                 // n+1 flat offsets
     const int32_t* first_tensor;        // lookup: first tensor per kLookupElems flat elements
-    float lr, mu, wd;
+    mc::UpdateParams up;
 };
 
 template <bool NT>
@@ -71,17 +72,6 @@ __device__ __forceinline__ void store4(float* p, const float4& q) {
     }
 }
 
-// Each line is one rounding to binary32 (the file is compiled without contraction).
-__device__ __forceinline__ void sgd(float g, float& w, float& v, float lr, float mu, float wd) {
-    const float decay = wd * w;
-    const float d = g + decay;
-    const float mv = mu * v;
-    const float vn = mv + d;
-    const float step = lr * vn;
-    w = w - step;
-    v = vn;
-}
-
 __device__ __forceinline__ bool aligned16(const void* p) {
     return (reinterpret_cast<uintptr_t>(p) & 15) == 0;
 }
@@ -91,6 +81,7 @@ template <int P, int U, bool HAS_G, bool NT>
 __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int Prt) {
     constexpr int64_t kTile = int64_t(kThreads) * 4 * U;
     const int np = P > 0 ? P : Prt;
+    const mc::Hyper hp = mc::resolve(a.up);
 
     int s = 0;
     while (s + 1 < a.n_segs && int(blockIdx.x) >= a.first_block[s + 1]) ++s;
@@ -144,10 +135,10 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
                         acc.w = acc.w + t[q][u].w;
                     }
                     if (HAS_G) store4<NT>(a.g + base + j[u], acc);
-                    sgd(acc.x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
-                    sgd(acc.y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
-                    sgd(acc.z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
-                    sgd(acc.w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
+                    mc::sgd(acc.x, wv[u].x, vv[u].x, hp);
+                    mc::sgd(acc.y, wv[u].y, vv[u].y, hp);
+                    mc::sgd(acc.z, wv[u].z, vv[u].z, hp);
+                    mc::sgd(acc.w, wv[u].w, vv[u].w, hp);
                     *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
                     *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
                 }
@@ -179,10 +170,10 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (HAS_G) store4<NT>(a.g + base + j[u], acc[u]);
-                    sgd(acc[u].x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
-                    sgd(acc[u].y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
-                    sgd(acc[u].z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
-                    sgd(acc[u].w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
+                    mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
+                    mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
+                    mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
+                    mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
                     *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
                     *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
                 }
@@ -217,10 +208,10 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
             float4 wq = *reinterpret_cast<const float4*>(wp);
             float4 vq = *reinterpret_cast<const float4*>(vp);
             if (HAS_G) *reinterpret_cast<float4*>(a.g + i) = acc;
-            sgd(acc.x, wq.x, vq.x, a.lr, a.mu, a.wd);
-            sgd(acc.y, wq.y, vq.y, a.lr, a.mu, a.wd);
-            sgd(acc.z, wq.z, vq.z, a.lr, a.mu, a.wd);
-            sgd(acc.w, wq.w, vq.w, a.lr, a.mu, a.wd);
+            mc::sgd(acc.x, wq.x, vq.x, hp);
+            mc::sgd(acc.y, wq.y, vq.y, hp);
+            mc::sgd(acc.z, wq.z, vq.z, hp);
+            mc::sgd(acc.w, wq.w, vq.w, hp);
             *reinterpret_cast<float4*>(wp) = wq;
             *reinterpret_cast<float4*>(vp) = vq;
         } else {
@@ -232,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
                 for (int q = 1; q < np; ++q) acc = acc + xs[q][t][r];
                 float we = a.w[t][r], ve = a.v[t][r];
                 if (HAS_G) a.g[e] = acc;
-                sgd(acc, we, ve, a.lr, a.mu, a.wd);
+                mc::sgd(acc, we, ve, hp);
                 a.w[t][r] = we;
                 a.v[t][r] = ve;
             }
@@ -359,10 +350,11 @@ int mc_tensor_set_destroy(mc_tensor_set* S) {
     return rc;
 }
 
-int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
-                  void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
-                  float lr, float mu, float wd, void* stream) {
+static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const mc::UpdateParams& up, void* stream) {
     if (!L || !contrib || !weights || !momentum || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if (up.hyper && !mc::aligned(up.hyper, 4)) return MC_ERR_ALIGN;
     if (weights->layout != L || momentum->layout != L) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
         if (!contrib[p] || contrib[p]->layout != L) return MC_ERR_INVALID_ARG;
@@ -417,9 +409,7 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
     a.g = static_cast<float*>(grad_out);
     a.off = dt->off;
     a.first_tensor = dt->tile_first;
-    a.lr = lr;
-    a.mu = mu;
-    a.wd = wd;
+    a.up = up;
     int32_t c = 0;
     while (c < L->k) {
         int ns = 0;
@@ -454,6 +444,27 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
         MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
+}
+
+int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                  void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                  float lr, float mu, float wd, void* stream) {
+    mc::UpdateParams up;
+    up.lr = lr;
+    up.mu = mu;
+    up.wd = wd;
+    up.hyper = nullptr;
+    up.nesterov = 0;
+    return fused_run(L, contrib, P, order, grad_out, weights, momentum, up, stream);
+}
+
+int mc_fused_step_ex(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const mc_update_spec* spec, void* stream) {
+    mc::UpdateParams up;
+    const int rc = mc::update_params(spec, &up);
+    if (rc != MC_OK) return rc;
+    return fused_run(L, contrib, P, order, grad_out, weights, momentum, up, stream);
 }
 
 }  // extern "C"

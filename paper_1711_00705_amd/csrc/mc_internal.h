@@ -63,6 +63,10 @@ int device_tables(mc_layout* L, const DeviceTables** out);
 
 int option(int which);
 
+struct UpdateParams;
+// Validates a caller's spec and converts it to the kernels' argument form.
+int update_params(const mc_update_spec* spec, UpdateParams* out);
+
 }  // namespace mc
 
 #define MC_HIP_TRY(expr)                                  \

@@ -16,6 +16,7 @@
 #include <vector>
 
 #include "mc_internal.h"
+#include "mc_update.h"
 
 #pragma clang fp contract(off)
 
@@ -34,7 +35,7 @@ struct RuArgs {
     float* g;                       // may be null when UPDATE
     float* w;                       // unused when !UPDATE
     float* v;
-    float lr, mu, wd;
+    mc::UpdateParams up;
 };
 
 template <bool NT>
@@ -62,17 +63,6 @@ __device__ __forceinline__ void store4(float* p, const float4& q) {
     }
 }
 
-// The update of one element; returns nothing, rewrites w and v.  Each line is one rounding.
-__device__ __forceinline__ void sgd(float g, float& w, float& v, float lr, float mu, float wd) {
-    const float decay = wd * w;
-    const float d = g + decay;
-    const float mv = mu * v;
-    const float vn = mv + d;
-    const float step = lr * vn;
-    w = w - step;
-    v = vn;
-}
-
 // P > 0: compile-time number of terms; P == 0: run-time count in `Prt` (up to MC_MAX_P).
 // UPDATE: the SGD step follows the sum (the rank holds the complete sum of these colours);
 // otherwise only the sum is written to g and w, v are never touched.
@@ -83,6 +73,7 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
     constexpr bool NT_IN = NT, NT_G = NT;
     constexpr int64_t kTile = int64_t(THREADS) * 4 * U;
     const int np = P > 0 ? P : Prt;
+    const mc::Hyper hp = mc::resolve(a.up);
 
     // blockIdx -> (segment, tile); a handful of scalar compares.
     int s = 0;
@@ -147,10 +138,10 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
         for (int u = 0; u < U; ++u) {
             if (HAS_G) store4<NT_G>(a.g + idx[u], acc[u]);
             if (UPDATE) {
-                sgd(acc[u].x, wv[u].x, vv[u].x, a.lr, a.mu, a.wd);
-                sgd(acc[u].y, wv[u].y, vv[u].y, a.lr, a.mu, a.wd);
-                sgd(acc[u].z, wv[u].z, vv[u].z, a.lr, a.mu, a.wd);
-                sgd(acc[u].w, wv[u].w, vv[u].w, a.lr, a.mu, a.wd);
+                mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
+                mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
+                mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
+                mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
                 *reinterpret_cast<float4*>(a.w + idx[u]) = wv[u];
                 *reinterpret_cast<float4*>(a.v + idx[u]) = vv[u];
             }
@@ -176,10 +167,10 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
             if (UPDATE) {
                 float4 wq = *reinterpret_cast<const float4*>(a.w + i);
                 float4 vq = *reinterpret_cast<const float4*>(a.v + i);
-                sgd(acc.x, wq.x, vq.x, a.lr, a.mu, a.wd);
-                sgd(acc.y, wq.y, vq.y, a.lr, a.mu, a.wd);
-                sgd(acc.z, wq.z, vq.z, a.lr, a.mu, a.wd);
-                sgd(acc.w, wq.w, vq.w, a.lr, a.mu, a.wd);
+                mc::sgd(acc.x, wq.x, vq.x, hp);
+                mc::sgd(acc.y, wq.y, vq.y, hp);
+                mc::sgd(acc.z, wq.z, vq.z, hp);
+                mc::sgd(acc.w, wq.w, vq.w, hp);
                 *reinterpret_cast<float4*>(a.w + i) = wq;
                 *reinterpret_cast<float4*>(a.v + i) = vq;
             }
@@ -190,7 +181,7 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
                 if (HAS_G) a.g[e] = acc;
                 if (UPDATE) {
                     float we = a.w[e], ve = a.v[e];
-                    sgd(acc, we, ve, a.lr, a.mu, a.wd);
+                    mc::sgd(acc, we, ve, hp);
                     a.w[e] = we;
                     a.v[e] = ve;
                 }
@@ -245,8 +236,9 @@ void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_
 // N), so every segment still starts on a 16-byte boundary.
 int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
         const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
-        void* momentum, float lr, float mu, float wd, int64_t r_lo, int64_t r_hi, void* stream) {
+        void* momentum, const mc::UpdateParams& up, int64_t r_lo, int64_t r_hi, void* stream) {
     if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if (up.hyper && !mc::aligned(up.hyper, 4)) return MC_ERR_ALIGN;
     if (r_lo < 0 || r_hi < r_lo || r_hi > L->N) return MC_ERR_INVALID_ARG;
     if (r_lo % MC_COLOUR_ALIGN_ELEMS != 0) return MC_ERR_INVALID_ARG;
     if (r_hi % MC_COLOUR_ALIGN_ELEMS != 0 && r_hi != L->N) return MC_ERR_INVALID_ARG;
@@ -299,9 +291,7 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
     a.g = static_cast<float*>(grad_out);
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);
-    a.lr = lr;
-    a.mu = mu;
-    a.wd = wd;
+    a.up = up;
 
     // Colours that add the same number of terms and agree on updating share launches (a rank is
     // inner node or root for at most one colour, so there are at most two such classes in
@@ -361,7 +351,31 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
     return MC_OK;
 }
 
+mc::UpdateParams immediate(float lr, float mu, float wd) {
+    mc::UpdateParams up;
+    up.lr = lr;
+    up.mu = mu;
+    up.wd = wd;
+    up.hyper = nullptr;
+    up.nesterov = 0;
+    return up;
+}
+
 }  // namespace
+
+namespace mc {
+
+int update_params(const mc_update_spec* spec, UpdateParams* out) {
+    if (!spec || (spec->nesterov != 0 && spec->nesterov != 1)) return MC_ERR_INVALID_ARG;
+    out->lr = spec->lr;
+    out->mu = spec->mu;
+    out->wd = spec->wd;
+    out->hyper = spec->hyper_dev;
+    out->nesterov = spec->nesterov;
+    return MC_OK;
+}
+
+}  // namespace mc
 
 extern "C" {
 
@@ -369,7 +383,8 @@ int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P, 
                      void* grad_out, void* weights, void* momentum, float lr, float mu, float wd,
                      void* stream) {
     if (!L) return MC_ERR_INVALID_ARG;
-    return run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, lr, mu, wd, 0, L->N, stream);
+    return run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, immediate(lr, mu, wd),
+               0, L->N, stream);
 }
 
 int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32_t P,
@@ -377,7 +392,8 @@ int mc_reduce_update_roles(const mc_layout* L, const void* const* contrib, int32
                            void* grad_out, void* weights, void* momentum, float lr, float mu,
                            float wd, void* stream) {
     if (!L || !n_terms || !do_update) return MC_ERR_INVALID_ARG;
-    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, lr, mu, wd, 0, L->N, stream);
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum,
+               immediate(lr, mu, wd), 0, L->N, stream);
 }
 
 int mc_reduce_update_range(const mc_layout* L, const void* const* contrib, int32_t P,
@@ -385,8 +401,20 @@ int mc_reduce_update_range(const mc_layout* L, const void* const* contrib, int32
                            void* grad_out, void* weights, void* momentum, float lr, float mu,
                            float wd, int64_t elem_begin, int64_t elem_end, void* stream) {
     if (!L) return MC_ERR_INVALID_ARG;
-    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, lr, mu, wd,
-               elem_begin, elem_end, stream);
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum,
+               immediate(lr, mu, wd), elem_begin, elem_end, stream);
+}
+
+int mc_reduce_update_ex(const mc_layout* L, const void* const* contrib, int32_t P,
+                        const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
+                        void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
+                        int64_t elem_begin, int64_t elem_end, void* stream) {
+    if (!L) return MC_ERR_INVALID_ARG;
+    mc::UpdateParams up;
+    const int rc = mc::update_params(spec, &up);
+    if (rc != MC_OK) return rc;
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up,
+               elem_begin, elem_end < 0 ? L->N : elem_end, stream);
 }
 
 }  // extern "C"

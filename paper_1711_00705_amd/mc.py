@@ -58,6 +58,13 @@ SIGNATURES = {
     "mc_tensor_set_destroy": (ctypes.c_int, [_vp]),
     "mc_fused_step": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
                                      ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_reduce_update_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
+                                           ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp, _vp,
+                                           ctypes.c_int64, ctypes.c_int64, _vp]),
+    "mc_fused_step_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp, _vp, _vp]),
+    "mc_hyper_write": (ctypes.c_int, [_vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
+    "mc_lr_schedule": (ctypes.c_int, [ctypes.c_float, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                      ctypes.c_float, ctypes.c_float, ctypes.POINTER(ctypes.c_float)]),
     "mc_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_int64, _vp]),
     "mc_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "mc_last_hip_error": (ctypes.c_int, []),
@@ -325,6 +332,67 @@ def fused_step(layout: Layout, contrib_sets, order, grad_out_ptr: Optional[int],
                              weights.handle if weights is not None else None,
                              momentum.handle if momentum is not None else None,
                              lr, mu, wd, stream or None), "mc_fused_step")
+
+
+class UpdateSpec(ctypes.Structure):
+    """mc_update_spec: immediate {lr, mu, wd} or a device pointer to them, and the Nesterov flag."""
+    _fields_ = [("lr", ctypes.c_float), ("mu", ctypes.c_float), ("wd", ctypes.c_float),
+                ("hyper_dev", ctypes.c_void_p), ("nesterov", ctypes.c_int32)]
+
+
+def update_spec(lr: float = 0.0, mu: float = 0.0, wd: float = 0.0, hyper_dev_ptr: Optional[int] = None,
+                nesterov: int = 0) -> UpdateSpec:
+    return UpdateSpec(lr, mu, wd, hyper_dev_ptr, int(nesterov))
+
+
+def _order_ptr(order, k: int, P: int):
+    if order is None:
+        return None, None
+    o = np.ascontiguousarray(order, dtype=np.int32)
+    if o.size != k * P:
+        raise ValueError("order must hold k_colours * P entries")
+    return o, o.ctypes.data_as(_i32p)
+
+
+def reduce_update_ex(layout: Layout, contrib_ptrs, order, grad_out_ptr, weights_ptr, momentum_ptr,
+                     spec: UpdateSpec, stream: int = 0, n_terms=None, do_update=None,
+                     elem_begin: int = 0, elem_end: int = -1) -> None:
+    P = _count(contrib_ptrs)
+    _o, optr = _order_ptr(order, layout.k, P)
+    ntp = dup = None
+    if n_terms is not None or do_update is not None:
+        nt = np.ascontiguousarray(n_terms, dtype=np.int32)
+        du = np.ascontiguousarray(do_update, dtype=np.uint8)
+        if nt.size != layout.k or du.size != layout.k:
+            raise ValueError("n_terms and do_update must hold k_colours entries")
+        ntp, dup = nt.ctypes.data_as(_i32p), du.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    _check(lib.mc_reduce_update_ex(layout.handle, _ptr_table(contrib_ptrs), P, optr, ntp, dup,
+                                   grad_out_ptr, weights_ptr, momentum_ptr,
+                                   ctypes.byref(spec) if spec is not None else None,
+                                   elem_begin, elem_end, stream or None), "mc_reduce_update_ex")
+
+
+def fused_step_ex(layout: Layout, contrib_sets, order, grad_out_ptr, weights: "TensorSet",
+                  momentum: "TensorSet", spec: UpdateSpec, stream: int = 0) -> None:
+    tab = contrib_sets if isinstance(contrib_sets, ctypes.Array) else set_table(contrib_sets)
+    _o, optr = _order_ptr(order, layout.k, tab.count)
+    _check(lib.mc_fused_step_ex(layout.handle, tab, tab.count, optr, grad_out_ptr,
+                                weights.handle if weights is not None else None,
+                                momentum.handle if momentum is not None else None,
+                                ctypes.byref(spec) if spec is not None else None, stream or None),
+           "mc_fused_step_ex")
+
+
+def hyper_write(hyper_dev_ptr: Optional[int], lr: float, mu: float, wd: float, stream: int = 0) -> None:
+    _check(lib.mc_hyper_write(hyper_dev_ptr, lr, mu, wd, stream or None), "mc_hyper_write")
+
+
+def lr_schedule(base_lr: float, batch_per_gpu: int, n_workers: int, warmup_epochs: float,
+                drop_every_epochs: float, epoch: float) -> float:
+    out = ctypes.c_float()
+    _check(lib.mc_lr_schedule(base_lr, batch_per_gpu, n_workers, warmup_epochs, drop_every_epochs,
+                              epoch, ctypes.byref(out)), "mc_lr_schedule")
+    return out.value
 
 
 def copy(dst_ptr: Optional[int], src_ptr: Optional[int], n_bytes: int, stream: int = 0) -> None:
