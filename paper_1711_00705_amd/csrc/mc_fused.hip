@@ -8,7 +8,9 @@
 // layer.  Workgroups walk colour segments in tiles; a tile that lies inside one tensor with
 // every operand 16-byte aligned (almost all tiles of a CNN payload) resolves its P + 2 base
 // pointers once and then runs the same 128-bit streaming loop as reduce_update; any other tile
-// takes a per-vector path that looks tensors up as it goes.
+// takes a per-vector path that looks tensors up as it goes.  Tiles whose operands share a non-zero
+// offset from a 16-byte boundary (everything after an odd-sized tensor) shift their vectors to the
+// operands' boundary instead and store only g word by word.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -72,14 +74,124 @@ __device__ __forceinline__ void store4(float* p, const float4& q) {
     }
 }
 
+// Offset of an address from the previous 16-byte boundary, in elements (0..3).
+__device__ __forceinline__ int misalignment(const void* p) {
+    return int((reinterpret_cast<uintptr_t>(p) >> 2) & 3);
+}
+
 __device__ __forceinline__ bool aligned16(const void* p) {
     return (reinterpret_cast<uintptr_t>(p) & 15) == 0;
+}
+
+// One element: the colour's sum in sequence, the update, the stores.
+template <bool HAS_G>
+__device__ __forceinline__ void one_element(const float* const* const* xs, int np, int32_t t, int64_t r,
+                                            float* const* w, float* const* v, float* g, int64_t e,
+                                            const mc::Hyper& hp) {
+    float acc = xs[0][t][r];
+    for (int q = 1; q < np; ++q) acc = acc + xs[q][t][r];
+    float we = w[t][r], ve = v[t][r];
+    if (HAS_G) g[e] = acc;
+    mc::sgd(acc, we, ve, hp);
+    w[t][r] = we;
+    v[t][r] = ve;
+}
+
+// A whole tile that lies inside tensor t0, all operands sharing one alignment.  `rel` is the
+// tensor-relative index of the first vectorised element (a 16-byte boundary of every operand),
+// gp the matching position in the flat gradient.  SHIFTED: that boundary is not the tile's first
+// element, so gp is not 16-byte aligned (g is stored word by word) and the tile has one vector
+// less (n_vec); the few elements before and after the vectors are done by the caller.
+template <int P, int U, bool HAS_G, bool NT, bool SHIFTED>
+__device__ __forceinline__ void uniform_tile(const float* const* const* xs, int np, int32_t t0, int64_t rel,
+                                             float* wp, float* vp, float* gp, int n_vec,
+                                             const mc::Hyper& hp) {
+    int64_t j[U];
+    bool on[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int jv = u * kThreads + int(threadIdx.x);
+        on[u] = !SHIFTED || jv < n_vec;
+        j[u] = int64_t(jv) * 4;
+    }
+    float4 acc[U], wv[U], vv[U];
+    if (P > 0) {
+        float4 t[P > 0 ? P : 1][U];
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            const float* xq = xs[q][t0] + rel;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (on[u]) t[q][u] = load4<NT>(xq + j[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (on[u]) {
+                wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
+                vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc[u] = t[0][u];
+#pragma unroll
+            for (int q = 1; q < P; ++q) {
+                acc[u].x = acc[u].x + t[q][u].x;
+                acc[u].y = acc[u].y + t[q][u].y;
+                acc[u].z = acc[u].z + t[q][u].z;
+                acc[u].w = acc[u].w + t[q][u].w;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (on[u]) {
+                wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
+                vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
+                acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
+            }
+        }
+        for (int q = 1; q < np; ++q) {
+            const float* xq = xs[q][t0] + rel;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (on[u]) {
+                    const float4 t = load4<NT>(xq + j[u]);
+                    acc[u].x = acc[u].x + t.x;
+                    acc[u].y = acc[u].y + t.y;
+                    acc[u].z = acc[u].z + t.z;
+                    acc[u].w = acc[u].w + t.w;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!on[u]) continue;
+        if (HAS_G) {
+            if (SHIFTED) {
+                float* gq = gp + j[u];
+                gq[0] = acc[u].x;
+                gq[1] = acc[u].y;
+                gq[2] = acc[u].z;
+                gq[3] = acc[u].w;
+            } else {
+                store4<NT>(gp + j[u], acc[u]);
+            }
+        }
+        mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
+        mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
+        mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
+        mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
+        *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
+        *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
+    }
 }
 
 // P > 0: compile-time number of terms; P == 0: run-time count in Prt.
 template <int P, int U, bool HAS_G, bool NT>
 __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int Prt) {
-    constexpr int64_t kTile = int64_t(kThreads) * 4 * U;
+    constexpr int kTile = kThreads * 4 * U;
     const int np = P > 0 ? P : Prt;
     const mc::Hyper hp = mc::resolve(a.up);
 
@@ -98,91 +210,36 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
     const int64_t t0_end = a.off[t0 + 1];
 
     if (end - base == kTile && end <= t0_end) {
-        // Whole tile inside tensor t0: resolve the base pointers once.
+        // Whole tile inside tensor t0.  If every operand has the same offset from a 16-byte
+        // boundary (all zero for a CNN payload; equal and non-zero after an odd-sized tensor,
+        // because frameworks align the tensors themselves), the tile runs on 128-bit accesses.
         const int64_t rel = base - t0_begin;
         float* wp = a.w[t0] + rel;
         float* vp = a.v[t0] + rel;
-        bool all_aligned = aligned16(wp) && aligned16(vp);
-        if (P > 0) {
-            const float* xp[P > 0 ? P : 1];
-#pragma unroll
-            for (int q = 0; q < P; ++q) {
-                xp[q] = xs[q][t0] + rel;
-                all_aligned = all_aligned && aligned16(xp[q]);
+        const int m = misalignment(wp);
+        bool same = misalignment(vp) == m;
+        for (int q = 0; q < np; ++q) same = same && misalignment(xs[q][t0] + rel) == m;
+        if (same && m == 0) {
+            uniform_tile<P, U, HAS_G, NT, false>(xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
+            return;
+        }
+        if (same) {
+            const int head = 4 - m;               // elements up to the operands' 16-byte boundary
+            const int n_vec = kTile / 4 - 1;      // whole vectors after it
+            uniform_tile<P, U, HAS_G, NT, true>(xs, np, t0, rel + head, wp + head, vp + head,
+                                                a.g + base + head, n_vec, hp);
+            // the `head` elements before the vectors and the `4 - head` after them
+            if (threadIdx.x < 4) {
+                const int e = int(threadIdx.x) < head ? int(threadIdx.x)
+                                                      : head + 4 * n_vec + (int(threadIdx.x) - head);
+                one_element<HAS_G>(xs, np, t0, rel + e, a.w, a.v, a.g, base + e, hp);
             }
-            if (all_aligned) {
-                float4 t[P > 0 ? P : 1][U], wv[U], vv[U];
-                int64_t j[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) j[u] = (int64_t(u) * kThreads + threadIdx.x) * 4;
-#pragma unroll
-                for (int q = 0; q < P; ++q)
-#pragma unroll
-                    for (int u = 0; u < U; ++u) t[q][u] = load4<NT>(xp[q] + j[u]);
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
-                    vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    float4 acc = t[0][u];
-#pragma unroll
-                    for (int q = 1; q < P; ++q) {
-                        acc.x = acc.x + t[q][u].x;
-                        acc.y = acc.y + t[q][u].y;
-                        acc.z = acc.z + t[q][u].z;
-                        acc.w = acc.w + t[q][u].w;
-                    }
-                    if (HAS_G) store4<NT>(a.g + base + j[u], acc);
-                    mc::sgd(acc.x, wv[u].x, vv[u].x, hp);
-                    mc::sgd(acc.y, wv[u].y, vv[u].y, hp);
-                    mc::sgd(acc.z, wv[u].z, vv[u].z, hp);
-                    mc::sgd(acc.w, wv[u].w, vv[u].w, hp);
-                    *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
-                    *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
-                }
-                return;
-            }
-        } else {
-            for (int q = 0; q < np; ++q) all_aligned = all_aligned && aligned16(xs[q][t0] + rel);
-            if (all_aligned) {
-                float4 acc[U], wv[U], vv[U];
-                int64_t j[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    j[u] = (int64_t(u) * kThreads + threadIdx.x) * 4;
-                    wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
-                    vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
-                    acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
-                }
-                for (int q = 1; q < np; ++q) {
-                    const float* xq = xs[q][t0] + rel;
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const float4 t = load4<NT>(xq + j[u]);
-                        acc[u].x = acc[u].x + t.x;
-                        acc[u].y = acc[u].y + t.y;
-                        acc[u].z = acc[u].z + t.z;
-                        acc[u].w = acc[u].w + t.w;
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (HAS_G) store4<NT>(a.g + base + j[u], acc[u]);
-                    mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
-                    mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
-                    mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
-                    mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-                    *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
-                    *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
-                }
-                return;
-            }
+            return;
         }
     }
 
-    // General tile: tensor boundaries, the ragged end of the segment, or misaligned operands.
+    // General tile: tensor boundaries, the ragged end of the segment, or operands whose
+    // alignments differ.
     for (int u = 0; u < U; ++u) {
         const int64_t i = base + (int64_t(u) * kThreads + threadIdx.x) * 4;
         if (i >= end) break;
@@ -218,14 +275,7 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
             const int64_t stop = i + 4 < end ? i + 4 : end;
             for (int64_t e = i; e < stop; ++e) {
                 while (a.off[t + 1] <= e) ++t;
-                const int64_t r = e - a.off[t];
-                float acc = xs[0][t][r];
-                for (int q = 1; q < np; ++q) acc = acc + xs[q][t][r];
-                float we = a.w[t][r], ve = a.v[t][r];
-                if (HAS_G) a.g[e] = acc;
-                mc::sgd(acc, we, ve, hp);
-                a.w[t][r] = we;
-                a.v[t][r] = ve;
+                one_element<HAS_G>(xs, np, t, e - a.off[t], a.w, a.v, a.g, e, hp);
             }
         }
     }

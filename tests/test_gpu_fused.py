@@ -182,6 +182,21 @@ def test_full_size_fused(name, order_kind):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("bump", [1, 2, 3])
+def test_full_size_odd_layout(bump):
+    """ResNet-50's tensors each `bump` elements longer: every flat offset after the first tensor
+    is misaligned while the tensors themselves stay 16-byte aligned (the shifted-vector path)."""
+    base = wl.workload("resnet50")
+    sizes = [s + bump for s in base.sizes]
+    print(f"fused odd layout bump={bump} N={sum(sizes)}", flush=True)
+    st = gh.FusedStep(sizes, 4)
+    xs = [wl.contribution_tensors(sizes, p) for p in range(4)]
+    gpu, ref = st.run(xs, wl.weight_tensors(sizes), wl.zero_tensors(sizes), 0.1, 0.9, 1e-4,
+                      order=wl.rotation_order(4, 4))
+    st.check(gpu, ref, f"fused odd layout bump={bump}")
+    torch.cuda.empty_cache()
+
+
 def test_googlenet_fused_steps_carry_state():
     cfg = wl.workload("googlenet")
     L = mc.Layout(cfg.sizes, cfg.k)
