@@ -62,6 +62,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pipeline-packets", type=int, default=0,
                     help="also run the packet-pipelined experiment with this many packets per colour")
+    ap.add_argument("--unroll", type=int, default=0, choices=[0, 1, 2],
+                    help="16-byte vectors per thread per tile (0 = the library picks from the size)")
     ap.add_argument("--kernel-only", action="store_true",
                     help="time only mc_reduce_update launches (for profiler runs)")
     return ap.parse_args()
@@ -235,6 +237,8 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.unroll:
+        mc.set_option(mc.OPT_RU_UNROLL, args.unroll)
     cfg = wl.workload(args.workload)
     N, P, k = cfg.total, cfg.P, cfg.k
     order = None if args.order == "identity" else wl.rotation_order(k, P)

@@ -273,7 +273,7 @@ int mc_last_hip_error(void);           /* raw hipError_t of this thread's last M
  * Returns MC_ERR_INVALID_ARG for an unknown option or a value outside its range. */
 enum {
     MC_OPT_RU_UNROLL = 1,          /* 16-byte vectors per thread per tile in reduce_update and
-                                      fused_step: 1 or 2 */
+                                      fused_step: 1 or 2; 0 (default) = chosen from the size */
     MC_OPT_RU_NONTEMPORAL = 2,     /* 0 / 1: streaming (non-temporal) loads of the contributions
                                       and store of grad_out.  Weights and momentum always use
                                       the normal policy so that they stay cached. */

@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <new>
 #include <vector>
 
 #include "mc_internal.h"
@@ -400,7 +401,7 @@ int mc_tensor_set_destroy(mc_tensor_set* S) {
     return rc;
 }
 
-static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
                      void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
                      const mc::UpdateParams& up, void* stream) {
     if (!L || !contrib || !weights || !momentum || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
@@ -447,7 +448,7 @@ static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t 
     for (int32_t p = 0; p < P; ++p)
         if (contrib[p]->device != dev) return MC_ERR_INVALID_ARG;
 
-    const int unroll = mc::option(MC_OPT_RU_UNROLL);
+    const int unroll = mc::unroll_for(L->N);
     const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
     const int64_t tile = int64_t(kThreads) * 4 * unroll;
     const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / P);
@@ -494,6 +495,17 @@ static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t 
         MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
+}
+
+// No C++ exception may cross the C boundary.
+static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
+                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const mc::UpdateParams& up, void* stream) {
+    try {
+        return fused_run_impl(L, contrib, P, order, grad_out, weights, momentum, up, stream);
+    } catch (const std::bad_alloc&) {
+        return MC_ERR_ALLOC;
+    }
 }
 
 int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,

@@ -62,6 +62,8 @@ inline bool overlaps(const void* a, uint64_t na, const void* b, uint64_t nb) {
 int device_tables(mc_layout* L, const DeviceTables** out);
 
 int option(int which);
+// Vectors per thread per tile for a launch over `elems` elements (honours MC_OPT_RU_UNROLL).
+int unroll_for(int64_t elems);
 
 struct UpdateParams;
 // Validates a caller's spec and converts it to the kernels' argument form.

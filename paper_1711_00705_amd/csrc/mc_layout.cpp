@@ -9,7 +9,7 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-std::atomic<int> g_ru_unroll{2};
+std::atomic<int> g_ru_unroll{0};
 std::atomic<int> g_ru_nontemporal{1};
 std::atomic<int> g_pack_nontemporal{3};
 
@@ -20,6 +20,15 @@ namespace mc {
 int hip_fail(hipError_t e) {
     g_last_hip_error = static_cast<int>(e);
     return MC_ERR_HIP;
+}
+
+int unroll_for(int64_t elems) {
+    const int u = g_ru_unroll.load(std::memory_order_relaxed);
+    if (u != 0) return u;
+    // Two vectors per thread once the grid still has several rounds of workgroups per compute
+    // unit; one below that, where a finer grid fills the chip more evenly (measured: GoogLeNet
+    // 45.1 -> 43.3 us, ResNet-50 within 0.5 % either way).
+    return elems / 2048 >= 8192 ? 2 : 1;
 }
 
 int option(int which) {
@@ -126,7 +135,7 @@ int mc_last_hip_error(void) { return g_last_hip_error; }
 int mc_set_option(int option, int value) {
     switch (option) {
         case MC_OPT_RU_UNROLL:
-            if (value != 1 && value != 2) return MC_ERR_INVALID_ARG;
+            if (value != 0 && value != 1 && value != 2) return MC_ERR_INVALID_ARG;
             g_ru_unroll.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_RU_NONTEMPORAL:

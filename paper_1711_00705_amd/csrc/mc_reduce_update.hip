@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <new>
 #include <vector>
 
 #include "mc_internal.h"
@@ -234,9 +235,9 @@ void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_
 // [r_lo, r_hi) restricts the call to a sub-range of the payload (a packet): every colour is
 // intersected with it.  r_lo and r_hi are multiples of the colour alignment (r_hi may also be
 // N), so every segment still starts on a 16-byte boundary.
-int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
-        const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
-        void* momentum, const mc::UpdateParams& up, int64_t r_lo, int64_t r_hi, void* stream) {
+int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
+             const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
+             void* momentum, const mc::UpdateParams& up, int64_t r_lo, int64_t r_hi, void* stream) {
     if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
     if (up.hyper && !mc::aligned(up.hyper, 4)) return MC_ERR_ALIGN;
     if (r_lo < 0 || r_hi < r_lo || r_hi > L->N) return MC_ERR_INVALID_ARG;
@@ -282,7 +283,7 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
         for (int j = i + 1; j < nb; ++j)
             if (mc::overlaps(bufs[i], bytes, bufs[j], bytes)) return MC_ERR_OVERLAP;
 
-    const int unroll = mc::option(MC_OPT_RU_UNROLL);
+    const int unroll = mc::unroll_for(r_hi - r_lo);
     const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
     const int64_t tile = int64_t(kThreads) * 4 * unroll;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -349,6 +350,18 @@ int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t
         }
     }
     return MC_OK;
+}
+
+// No C++ exception may cross the C boundary.
+int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
+        const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
+        void* momentum, const mc::UpdateParams& up, int64_t r_lo, int64_t r_hi, void* stream) {
+    try {
+        return run_impl(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up,
+                        r_lo, r_hi, stream);
+    } catch (const std::bad_alloc&) {
+        return MC_ERR_ALLOC;
+    }
 }
 
 mc::UpdateParams immediate(float lr, float mu, float wd) {

@@ -153,8 +153,8 @@ def test_empty_payload_is_a_no_op():
 
 
 def test_options():
-    assert mc.get_option(mc.OPT_RU_UNROLL) in (1, 2)
-    for opt, good, bad in ((mc.OPT_RU_UNROLL, (1, 2), (0, 3, 4)),
+    assert mc.get_option(mc.OPT_RU_UNROLL) in (0, 1, 2)
+    for opt, good, bad in ((mc.OPT_RU_UNROLL, (0, 1, 2), (-1, 3, 4)),
                            (mc.OPT_RU_NONTEMPORAL, (0, 1), (-1, 2)),
                            (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4))):
         keep = mc.get_option(opt)
