@@ -17,8 +17,9 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kVecPerThread = int(mc::kPackTileElems / 4 / kThreads);  // 16-byte vectors per thread
-static_assert(mc::kPackTileElems == int64_t(kThreads) * 4 * kVecPerThread, "tile shape");
+constexpr int kMaxVecPerThread = int(mc::kPackTileElems / 4 / kThreads);  // 16-byte vectors per thread
+static_assert(mc::kPackTileElems == int64_t(kThreads) * 4 * kMaxVecPerThread, "tile shape");
+static_assert(kMaxVecPerThread == 2, "the launch code below instantiates V = 1 and V = 2");
 
 struct PtrBatch {
     void* p[mc::kPackMaxPtrs];
@@ -52,18 +53,21 @@ __device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
 // One launch covers tensors [t0, t1), i.e. flat elements [off[t0], off[t1]), tile by tile.
 // UNPACK = false: tensors -> flat.  UNPACK = true: flat -> tensors.
 // NT_T / NT_F: streaming (non-temporal) policy for the tensor side / the flat side.
-template <bool UNPACK, bool NT_T, bool NT_F>
+// V: 16-byte vectors per thread; a workgroup covers a tile of kThreads * 4 * V flat elements.
+template <bool UNPACK, bool NT_T, bool NT_F, int V>
 __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
     PtrBatch ptrs, const int64_t* __restrict__ off, const int32_t* __restrict__ tile_first,
     uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0) {
+    constexpr int64_t kTileElems = int64_t(kThreads) * 4 * V;
+    static_assert(kTileElems % mc::kLookupElems == 0, "tiles start on lookup entries");
     const int64_t tile = tile0 + blockIdx.x;
     const int64_t lo = off[t0];
     const int64_t hi = off[t1];
-    const int64_t tile_base = tile * mc::kPackTileElems;
+    const int64_t tile_base = tile * kTileElems;
     const int32_t t_tile = max(tile_first[tile_base / mc::kLookupElems], t0);
 
 #pragma unroll
-    for (int j = 0; j < kVecPerThread; ++j) {
+    for (int j = 0; j < V; ++j) {
         const int64_t i = tile_base + (int64_t(j) * kThreads + threadIdx.x) * 4;
         if (i >= hi || i + 4 <= lo) continue;
         const int64_t first = i > lo ? i : lo;
@@ -136,16 +140,29 @@ int run(mc_layout* L, void* const* tensors, void* flat, void* stream) {
         PtrBatch batch;
         for (int32_t t = t0; t < t1; ++t) batch.p[t - t0] = tensors[t];
         for (int32_t t = t1 - t0; t < mc::kPackMaxPtrs; ++t) batch.p[t] = nullptr;
-        const int64_t tile0 = lo / mc::kPackTileElems;
-        const int64_t tile_end = (hi + mc::kPackTileElems - 1) / mc::kPackTileElems;
+        // Small payloads use the finer tile so that the grid still fills the chip evenly.
+        const int vec = L->N / mc::kPackTileElems >= 8192 ? 2 : 1;
+        const int64_t tile_elems = int64_t(kThreads) * 4 * vec;
+        const int64_t tile0 = lo / tile_elems;
+        const int64_t tile_end = (hi + tile_elems - 1) / tile_elems;
         const dim3 grid(unsigned(tile_end - tile0)), block(kThreads);
         uint32_t* f = static_cast<uint32_t*>(flat);
+#define MC_GS_LAUNCH(NT_T, NT_F)                                                                       \
+    do {                                                                                               \
+        if (vec == 2)                                                                                  \
+            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, 0, s, batch, \
+                               dt->off, dt->tile_first, f, t0, t1, tile0);                             \
+        else                                                                                           \
+            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, 0, s, batch, \
+                               dt->off, dt->tile_first, f, t0, t1, tile0);                             \
+    } while (0)
         switch (nt & 3) {
-            case 0: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, false, false>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
-            case 1: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, true, false>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
-            case 2: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, false, true>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
-            default: hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, true, true>), grid, block, 0, s, batch, dt->off, dt->tile_first, f, t0, t1, tile0); break;
+            case 0: MC_GS_LAUNCH(false, false); break;
+            case 1: MC_GS_LAUNCH(true, false); break;
+            case 2: MC_GS_LAUNCH(false, true); break;
+            default: MC_GS_LAUNCH(true, true); break;
         }
+#undef MC_GS_LAUNCH
         MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
