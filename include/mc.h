@@ -277,8 +277,11 @@ enum {
     MC_OPT_RU_NONTEMPORAL = 2,     /* 0 / 1: streaming (non-temporal) loads of the contributions
                                       and store of grad_out.  Weights and momentum always use
                                       the normal policy so that they stay cached. */
-    MC_OPT_PACK_NONTEMPORAL = 3    /* pack/unpack: bit 0 streaming access to the per-layer
-                                      tensors, bit 1 streaming access to the flat payload */
+    MC_OPT_PACK_NONTEMPORAL = 3,   /* pack/unpack: bit 0 streaming access to the per-layer
+                                      tensors, bit 1 streaming access to the flat payload
+                                      (non-temporal loads, write-through stores) */
+    MC_OPT_STATE_STORE_SC1 = 4     /* 0 / 1: full tiles store updated weights and momentum with the
+                                      agent-scope (write-through) bit */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

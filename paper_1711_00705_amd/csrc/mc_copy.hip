@@ -1,7 +1,7 @@
 // A plain 128-bit device-to-device copy: the yardstick the other kernels are measured
 // against (achievable HBM bandwidth) and the known-size traffic used to calibrate hardware
-// counters.  One 16-byte vector per thread, streaming (non-temporal) load and store: the
-// fastest of the plain copies measured on this part.
+// counters.  One 16-byte vector per thread, non-temporal load and write-through (agent-scope)
+// store: the fastest of the plain copies measured on this part.
 #include <hip/hip_runtime.h>
 
 #include "mc_internal.h"
@@ -19,22 +19,19 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(uint4* __restrict__ dst,
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t i = base + int64_t(j) * kThreads;
         if (i < n_vec) {
-            const uint32_t* p = reinterpret_cast<const uint32_t*>(src + i);
-            r[j].x = __builtin_nontemporal_load(p + 0);
-            r[j].y = __builtin_nontemporal_load(p + 1);
-            r[j].z = __builtin_nontemporal_load(p + 2);
-            r[j].w = __builtin_nontemporal_load(p + 3);
+            typedef uint32_t native4 __attribute__((ext_vector_type(4)));
+            const native4 t = __builtin_nontemporal_load(reinterpret_cast<const native4*>(src + i));
+            r[j] = make_uint4(t.x, t.y, t.z, t.w);
         }
     }
 #pragma unroll
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t i = base + int64_t(j) * kThreads;
         if (i < n_vec) {
-            uint32_t* p = reinterpret_cast<uint32_t*>(dst + i);
-            __builtin_nontemporal_store(r[j].x, p + 0);
-            __builtin_nontemporal_store(r[j].y, p + 1);
-            __builtin_nontemporal_store(r[j].z, p + 2);
-            __builtin_nontemporal_store(r[j].w, p + 3);
+            // (s_nop: wait states the hardware needs before the data registers may be rewritten)
+            typedef uint32_t native4 __attribute__((ext_vector_type(4)));
+            const native4 val = {r[j].x, r[j].y, r[j].z, r[j].w};
+            asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(dst + i), "v"(val) : "memory");
         }
     }
 }

@@ -50,30 +50,32 @@ struct FusedArgs {
     mc::UpdateParams up;
 };
 
+typedef float native_f4 __attribute__((ext_vector_type(4)));
+// Every tensor lives in device global memory.  Pointers read from a tensor set's table arrive as
+// generic pointers; dereferencing them through global-address-space types lets the compiler use
+// global_ instead of flat_ instructions.
+typedef __attribute__((address_space(1))) native_f4 global_f4;
+typedef __attribute__((address_space(1))) float global_f1;
+
 template <bool NT>
 __device__ __forceinline__ float4 load4(const float* p) {
-    if (NT) {
-        float4 r;
-        r.x = __builtin_nontemporal_load(p + 0);
-        r.y = __builtin_nontemporal_load(p + 1);
-        r.z = __builtin_nontemporal_load(p + 2);
-        r.w = __builtin_nontemporal_load(p + 3);
-        return r;
-    }
-    return *reinterpret_cast<const float4*>(p);
+    const global_f4* gp = (const global_f4*)p;
+    const native_f4 r = NT ? __builtin_nontemporal_load(gp) : *gp;
+    return make_float4(r.x, r.y, r.z, r.w);
 }
 
 template <bool NT>
 __device__ __forceinline__ void store4(float* p, const float4& q) {
-    if (NT) {
-        __builtin_nontemporal_store(q.x, p + 0);
-        __builtin_nontemporal_store(q.y, p + 1);
-        __builtin_nontemporal_store(q.z, p + 2);
-        __builtin_nontemporal_store(q.w, p + 3);
-    } else {
-        *reinterpret_cast<float4*>(p) = q;
-    }
+    const native_f4 val = {q.x, q.y, q.z, q.w};
+    global_f4* gp = (global_f4*)p;
+    if (NT)
+        __builtin_nontemporal_store(val, gp);
+    else
+        *gp = val;
 }
+
+__device__ __forceinline__ float ld1(const float* p) { return *(const global_f1*)p; }
+__device__ __forceinline__ void st1(float* p, float x) { *(global_f1*)p = x; }
 
 // Offset of an address from the previous 16-byte boundary, in elements (0..3).
 __device__ __forceinline__ int misalignment(const void* p) {
@@ -89,13 +91,15 @@ template <bool HAS_G>
 __device__ __forceinline__ void one_element(const float* const* const* xs, int np, int32_t t, int64_t r,
                                             float* const* w, float* const* v, float* g, int64_t e,
                                             const mc::Hyper& hp) {
-    float acc = xs[0][t][r];
-    for (int q = 1; q < np; ++q) acc = acc + xs[q][t][r];
-    float we = w[t][r], ve = v[t][r];
-    if (HAS_G) g[e] = acc;
+    float acc = ld1(xs[0][t] + r);
+    for (int q = 1; q < np; ++q) acc = acc + ld1(xs[q][t] + r);
+    float* wp = w[t] + r;
+    float* vp = v[t] + r;
+    float we = ld1(wp), ve = ld1(vp);
+    if (HAS_G) st1(g + e, acc);
     mc::sgd(acc, we, ve, hp);
-    w[t][r] = we;
-    v[t][r] = ve;
+    st1(wp, we);
+    st1(vp, ve);
 }
 
 // A whole tile that lies inside tensor t0, all operands sharing one alignment.  `rel` is the
@@ -128,8 +132,8 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (on[u]) {
-                wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
-                vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
+                wv[u] = load4<false>(wp + j[u]);
+                vv[u] = load4<false>(vp + j[u]);
             }
         }
 #pragma unroll
@@ -147,8 +151,8 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (on[u]) {
-                wv[u] = *reinterpret_cast<const float4*>(wp + j[u]);
-                vv[u] = *reinterpret_cast<const float4*>(vp + j[u]);
+                wv[u] = load4<false>(wp + j[u]);
+                vv[u] = load4<false>(vp + j[u]);
                 acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
             }
         }
@@ -172,10 +176,10 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
         if (HAS_G) {
             if (SHIFTED) {
                 float* gq = gp + j[u];
-                gq[0] = acc[u].x;
-                gq[1] = acc[u].y;
-                gq[2] = acc[u].z;
-                gq[3] = acc[u].w;
+                st1(gq + 0, acc[u].x);
+                st1(gq + 1, acc[u].y);
+                st1(gq + 2, acc[u].z);
+                st1(gq + 3, acc[u].w);
             } else {
                 store4<NT>(gp + j[u], acc[u]);
             }
@@ -184,8 +188,8 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
         mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
         mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
         mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-        *reinterpret_cast<float4*>(wp + j[u]) = wv[u];
-        *reinterpret_cast<float4*>(vp + j[u]) = vv[u];
+        mc::store_state(wp + j[u], wv[u], hp.state_store_sc1);
+        mc::store_state(vp + j[u], vv[u], hp.state_store_sc1);
     }
 }
 
@@ -263,15 +267,15 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
             }
             float* wp = a.w[t] + rel;
             float* vp = a.v[t] + rel;
-            float4 wq = *reinterpret_cast<const float4*>(wp);
-            float4 vq = *reinterpret_cast<const float4*>(vp);
-            if (HAS_G) *reinterpret_cast<float4*>(a.g + i) = acc;
+            float4 wq = load4<false>(wp);
+            float4 vq = load4<false>(vp);
+            if (HAS_G) store4<false>(a.g + i, acc);
             mc::sgd(acc.x, wq.x, vq.x, hp);
             mc::sgd(acc.y, wq.y, vq.y, hp);
             mc::sgd(acc.z, wq.z, vq.z, hp);
             mc::sgd(acc.w, wq.w, vq.w, hp);
-            *reinterpret_cast<float4*>(wp) = wq;
-            *reinterpret_cast<float4*>(vp) = vq;
+            store4<false>(wp, wq);
+            store4<false>(vp, vq);
         } else {
             const int64_t stop = i + 4 < end ? i + 4 : end;
             for (int64_t e = i; e < stop; ++e) {
@@ -517,6 +521,7 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
     up.wd = wd;
     up.hyper = nullptr;
     up.nesterov = 0;
+    up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
     return fused_run(L, contrib, P, order, grad_out, weights, momentum, up, stream);
 }
 

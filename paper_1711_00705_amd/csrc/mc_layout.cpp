@@ -12,6 +12,7 @@ thread_local int g_last_hip_error = 0;
 std::atomic<int> g_ru_unroll{0};
 std::atomic<int> g_ru_nontemporal{1};
 std::atomic<int> g_pack_nontemporal{3};
+std::atomic<int> g_state_store_sc1{1};
 
 }  // namespace
 
@@ -36,6 +37,7 @@ int option(int which) {
         case MC_OPT_RU_UNROLL: return g_ru_unroll.load(std::memory_order_relaxed);
         case MC_OPT_RU_NONTEMPORAL: return g_ru_nontemporal.load(std::memory_order_relaxed);
         case MC_OPT_PACK_NONTEMPORAL: return g_pack_nontemporal.load(std::memory_order_relaxed);
+        case MC_OPT_STATE_STORE_SC1: return g_state_store_sc1.load(std::memory_order_relaxed);
         default: return -1;
     }
 }
@@ -145,6 +147,10 @@ int mc_set_option(int option, int value) {
         case MC_OPT_PACK_NONTEMPORAL:
             if (value < 0 || value > 3) return MC_ERR_INVALID_ARG;
             g_pack_nontemporal.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_STATE_STORE_SC1:
+            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
+            g_state_store_sc1.store(value, std::memory_order_relaxed);
             return MC_OK;
         default:
             return MC_ERR_INVALID_ARG;

@@ -39,15 +39,13 @@ struct RuArgs {
     mc::UpdateParams up;
 };
 
+typedef float native_f4 __attribute__((ext_vector_type(4)));
+
 template <bool NT>
 __device__ __forceinline__ float4 load4(const float* p) {
     if (NT) {
-        float4 r;
-        r.x = __builtin_nontemporal_load(p + 0);
-        r.y = __builtin_nontemporal_load(p + 1);
-        r.z = __builtin_nontemporal_load(p + 2);
-        r.w = __builtin_nontemporal_load(p + 3);
-        return r;
+        const native_f4 r = __builtin_nontemporal_load(reinterpret_cast<const native_f4*>(p));
+        return make_float4(r.x, r.y, r.z, r.w);
     }
     return *reinterpret_cast<const float4*>(p);
 }
@@ -55,10 +53,8 @@ __device__ __forceinline__ float4 load4(const float* p) {
 template <bool NT>
 __device__ __forceinline__ void store4(float* p, const float4& q) {
     if (NT) {
-        __builtin_nontemporal_store(q.x, p + 0);
-        __builtin_nontemporal_store(q.y, p + 1);
-        __builtin_nontemporal_store(q.z, p + 2);
-        __builtin_nontemporal_store(q.w, p + 3);
+        const native_f4 val = {q.x, q.y, q.z, q.w};
+        __builtin_nontemporal_store(val, reinterpret_cast<native_f4*>(p));
     } else {
         *reinterpret_cast<float4*>(p) = q;
     }
@@ -143,8 +139,8 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
                 mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
                 mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
                 mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-                *reinterpret_cast<float4*>(a.w + idx[u]) = wv[u];
-                *reinterpret_cast<float4*>(a.v + idx[u]) = vv[u];
+                mc::store_state(a.w + idx[u], wv[u], hp.state_store_sc1);
+                mc::store_state(a.v + idx[u], vv[u], hp.state_store_sc1);
             }
         }
         return;
@@ -371,6 +367,7 @@ mc::UpdateParams immediate(float lr, float mu, float wd) {
     up.wd = wd;
     up.hyper = nullptr;
     up.nesterov = 0;
+    up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
     return up;
 }
 
@@ -385,6 +382,7 @@ int update_params(const mc_update_spec* spec, UpdateParams* out) {
     out->wd = spec->wd;
     out->hyper = spec->hyper_dev;
     out->nesterov = spec->nesterov;
+    out->state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
     return MC_OK;
 }
 

@@ -25,6 +25,7 @@ COLOUR_ALIGN_ELEMS = 256
 OPT_RU_UNROLL = 1
 OPT_RU_NONTEMPORAL = 2
 OPT_PACK_NONTEMPORAL = 3
+OPT_STATE_STORE_SC1 = 4
 ROLE_LEAF, ROLE_INNER, ROLE_ROOT = 0, 1, 2
 
 _i64p = ctypes.POINTER(ctypes.c_int64)

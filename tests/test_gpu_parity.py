@@ -17,7 +17,7 @@ import gpu_harness as gh  # noqa: E402
 
 @pytest.fixture(autouse=True)
 def _restore_options():
-    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL, mc.OPT_PACK_NONTEMPORAL)}
+    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL, mc.OPT_PACK_NONTEMPORAL, mc.OPT_STATE_STORE_SC1)}
     yield
     for o, v in keep.items():
         mc.set_option(o, v)
@@ -55,6 +55,7 @@ def test_tiny_config(order_kind, misalign):
 @pytest.mark.parametrize("nt", [0, 1])
 @pytest.mark.parametrize("pack_nt", [0, 1, 2, 3])
 def test_launch_shapes_do_not_change_bits(unroll, nt, pack_nt):
+    mc.set_option(mc.OPT_STATE_STORE_SC1, (unroll + nt + pack_nt) % 2)
     mc.set_option(mc.OPT_RU_UNROLL, unroll)
     mc.set_option(mc.OPT_PACK_NONTEMPORAL, pack_nt)
     mc.set_option(mc.OPT_RU_NONTEMPORAL, nt)
