@@ -62,6 +62,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pipeline-packets", type=int, default=0,
                     help="also run the packet-pipelined experiment with this many packets per colour")
+    ap.add_argument("--roles-nodes", type=int, default=0,
+                    help="also time one rank's role-dependent step in a tree Allreduce over this many nodes")
     ap.add_argument("--unroll", type=int, default=0, choices=[0, 1, 2],
                     help="16-byte vectors per thread per tile (0 = the library picks from the size)")
     ap.add_argument("--state-store-sc1", type=int, default=-1, choices=[-1, 0, 1],
@@ -140,6 +142,60 @@ def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, step
                      "sample": f"{n2} whole steps, one host thread per colour ({nthr}) / per pack ({cfg.P})"},
         "host_cpus": ncpu,
     }
+
+
+def roles_experiment(torch, mc, L, cfg, flats, g, w, v, stream, n_nodes, reps):
+    """One rank's real share in a k-colour tree Allreduce over n_nodes nodes (Section 4.2): it
+    is inner node or root of at most one colour and a leaf of the others.  Phase 1: per colour,
+    add the m local replicas (leaf) or those plus one buffer per child (inner node, root); only
+    the root's colour is updated at once.  Phase 2: the other colours are updated from the
+    broadcast sum (a single contribution).  m = the workload's P; child buffers are further
+    flat buffers of the same size.  Times both phases for the rank with the most work (an inner
+    node) and for a pure-leaf rank, with the algorithmic bytes of each."""
+    N, m, k = cfg.total, cfg.P, cfg.k
+    sh = int(stream.cuda_stream)
+    bounds = [int(b) for b in L.colour_bounds()]
+    lens = [bounds[c + 1] - bounds[c] for c in range(k)]
+    child_bufs = [torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3 for _ in range(k)]
+    contrib = mc.ptr_table([f.data_ptr() for f in flats] + [c.data_ptr() for c in child_bufs])
+    bcast = torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3
+    bcast_tab = mc.ptr_table([bcast.data_ptr()])
+    scratch = torch.empty(N, dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    out = {"n_nodes": n_nodes, "colours": k, "local_replicas": m, "ranks": {}}
+    picked = {}
+    for rank in range(n_nodes):
+        role, cnt, _children = mc.rank_roles(n_nodes, k, rank)
+        kind = "root" if (role == mc.ROLE_ROOT).any() else "inner" if (role == mc.ROLE_INNER).any() else "leaf"
+        picked.setdefault(kind, (rank, role, cnt))
+    for kind, (rank, role, cnt) in picked.items():
+        n_terms = [m + int(cnt[c]) for c in range(k)]
+        upd = [1 if role[c] == mc.ROLE_ROOT else 0 for c in range(k)]
+        later = [0 if role[c] == mc.ROLE_ROOT else 1 for c in range(k)]
+        bytes1 = sum(4 * lens[c] * (n_terms[c] + 1 + (4 if upd[c] else 0)) for c in range(k))
+        bytes2 = sum(4 * lens[c] * (1 + 4) for c in range(k) if later[c])
+        t1 = timed(lambda: mc.reduce_update_roles(L, contrib, None, n_terms, upd, g.data_ptr(), w.data_ptr(),
+                                                  v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, sh))
+        t2 = timed(lambda: mc.reduce_update_roles(L, bcast_tab, None, later, [1] * k, scratch.data_ptr(),
+                                                  w.data_ptr(), v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, sh)) \
+            if any(later) else 0.0
+        out["ranks"][kind] = {"rank": rank, "terms_per_colour": n_terms, "updates_at_once": upd,
+                              "sum_ms": round(t1, 4), "sum_GBps": round(bytes1 / t1 / 1e6, 1),
+                              "update_from_broadcast_ms": round(t2, 4),
+                              "update_GBps": round(bytes2 / t2 / 1e6, 1) if t2 else None}
+    return out
 
 
 def pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, stream, packets, reps):
@@ -420,6 +476,11 @@ def main():
         pipelined = pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, stream,
                                         args.pipeline_packets, reps=max(5, min(args.steps, 30)))
 
+    roles = None
+    if args.roles_nodes > 0:
+        roles = roles_experiment(torch, mc, L, cfg, flats, g, w, v, stream, args.roles_nodes,
+                                 reps=max(5, min(args.steps, 30)))
+
     k_avg = float(k_ms.mean())
     achieved = kernel_bytes / k_avg / 1e6
     staged_bytes = (8 * P + 4 * (P + 5) + 8) * N
@@ -463,6 +524,7 @@ def main():
                      "traffic": measured_traffic(kernel_name, cfg.name, P, k), "bytes_per_launch": kernel_bytes,
                      "kernel_ms": round(k_avg, 4)},
         "pipelined_packets": pipelined,
+        "roles": roles,
         "cpu_baseline": cpu,
         "parity_checked_first_step": cpu is not None,
         "library": os.path.relpath(mc.LIBRARY_PATH, ROOT),
