@@ -1,0 +1,29 @@
+"""bench.py's contract where no GPU is needed: more than one GPU is refused with a message,
+and the measured-traffic figures are read from the committed profile summaries."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="4")
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True,
+                         timeout=120, env=env)
+    assert res.returncode != 0 and "ONE GPU" in res.stderr
+
+
+def test_measured_traffic_comes_from_the_profile_summaries():
+    sys.path.insert(0, ROOT)
+    import bench
+    for kernel, wl_, P, k, algorithmic in (("fused_step_kernel", "resnet50", 4, 4, 920053152),
+                                           ("reduce_update_kernel", "resnet50", 4, 4, 920053152),
+                                           ("fused_step_kernel", "vgg16", 4, 4, 4980871584)):
+        t = bench.measured_traffic(kernel, wl_, P, k)
+        assert t is not None and 0.98 * algorithmic < t < 1.05 * algorithmic
+    assert bench.measured_traffic("fused_step_kernel", "no_such_workload", 4, 4) is None
