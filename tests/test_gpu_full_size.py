@@ -66,3 +66,42 @@ def test_googlenet_hundred_steps_carry_state():
     torch.cuda.synchronize()
     for a, b in zip(w_layers, oracle.unpack(O, wr)):
         gh.assert_bits(a.cpu().numpy(), b, "unpacked final weights")
+
+
+def test_full_size_roles_nesterov_device_hyper():
+    """ResNet-50 size through the most general entry point: per-colour term counts, update only
+    on two colours, Nesterov step, {lr, mu, wd} read from device memory."""
+    cfg = wl.workload("resnet50_heavy")
+    k, P = cfg.k, cfg.P
+    L = mc.Layout(cfg.sizes, k)
+    O = oracle.Layout(cfg.sizes, k)
+    N = L.N
+    print(f"full size roles/nesterov N={N} P={P} k={k}", flush=True)
+    rng = np.random.Generator(np.random.PCG64(11))
+    xs_h = [oracle.pack(O, wl.contribution_tensors(cfg.sizes, p, heavy_tail=True)) for p in range(P)]
+    w_h = oracle.pack(O, wl.weight_tensors(cfg.sizes))
+    v_h = rng.standard_normal(N, dtype=np.float32) * np.float32(0.01)
+    s = gh.stream_handle()
+    xd = [gh.to_dev(x) for x in xs_h]
+    w, v, g = gh.to_dev(w_h), gh.to_dev(v_h), gh.dev_empty(N)
+    hyper = gh.dev_empty(3)
+    mc.hyper_write(hyper.data_ptr(), cfg.lr, cfg.mu, cfg.wd, s)
+    # uniform call, Nesterov, device hyper-parameters
+    mc.reduce_update_ex(L, [x.data_ptr() for x in xd], wl.rotation_order(k, P), g.data_ptr(), w.data_ptr(),
+                        v.data_ptr(), mc.update_spec(hyper_dev_ptr=hyper.data_ptr(), nesterov=1), s)
+    torch.cuda.synchronize()
+    wr, vr = w_h.copy(), v_h.copy()
+    gr = oracle.reduce_update_nesterov(O, xs_h, wr, vr, cfg.lr, cfg.mu, cfg.wd, order=wl.rotation_order(k, P))
+    gh.assert_bits(g.cpu().numpy(), gr, "g (nesterov)")
+    gh.assert_bits(w.cpu().numpy(), wr, "w (nesterov)")
+    gh.assert_bits(v.cpu().numpy(), vr, "v (nesterov)")
+    # roles on top of that state: colours 0 and 5 update with all terms, colour 2 is skipped, the rest sum 4 terms
+    n_terms = np.array([P, 4, 0, 4, 4, P, 4, 4], np.int32)
+    do_update = np.array([1, 0, 1, 0, 0, 1, 0, 0], np.uint8)
+    mc.reduce_update_roles(L, [x.data_ptr() for x in xd], None, n_terms, do_update, g.data_ptr(), w.data_ptr(),
+                           v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, s)
+    torch.cuda.synchronize()
+    oracle.reduce_update_roles(O, xs_h, n_terms, do_update, gr, wr, vr, cfg.lr, cfg.mu, cfg.wd)
+    gh.assert_bits(g.cpu().numpy(), gr, "g (roles)")
+    gh.assert_bits(w.cpu().numpy(), wr, "w (roles)")
+    gh.assert_bits(v.cpu().numpy(), vr, "v (roles)")
