@@ -229,7 +229,10 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
  *   one).  Any other value: MC_ERR_INVALID_ARG.
  * mc_reduce_update_ex: the most general form of mc_reduce_update: n_terms / do_update both NULL or
  *   both given (as in _roles), range as in _range with elem_end < 0 meaning N.
- * mc_fused_step_ex: mc_fused_step with a spec.
+ * mc_fused_step_ex: mc_fused_step with a spec and with per-colour roles: n_terms / do_update both
+ *   NULL or both given, as in mc_reduce_update_roles (weights / momentum may be NULL when no colour
+ *   updates, grad_out when every non-skipped colour updates).  With flat receive buffers wrapped
+ *   as tensor sets this is a rank's whole step in a tree Allreduce without any staging copy.
  * mc_hyper_write: enqueues on `stream` a write of {lr, mu, wd} to hyper_dev (a one-thread kernel;
  *   no host memory is read after the call returns, nothing synchronises). */
 typedef struct mc_update_spec {
@@ -242,7 +245,8 @@ int mc_reduce_update_ex(const mc_layout* L, const void* const* contrib, int32_t 
                         void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
                         int64_t elem_begin, int64_t elem_end, void* stream);
 int mc_fused_step_ex(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
-                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
+                     const mc_tensor_set* weights, const mc_tensor_set* momentum,
                      const mc_update_spec* spec, void* stream);
 int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream);
 

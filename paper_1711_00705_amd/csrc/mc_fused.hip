@@ -87,19 +87,21 @@ __device__ __forceinline__ bool aligned16(const void* p) {
 }
 
 // One element: the colour's sum in sequence, the update, the stores.
-template <bool HAS_G>
+template <bool HAS_G, bool UPDATE>
 __device__ __forceinline__ void one_element(const float* const* const* xs, int np, int32_t t, int64_t r,
                                             float* const* w, float* const* v, float* g, int64_t e,
                                             const mc::Hyper& hp) {
     float acc = ld1(xs[0][t] + r);
     for (int q = 1; q < np; ++q) acc = acc + ld1(xs[q][t] + r);
-    float* wp = w[t] + r;
-    float* vp = v[t] + r;
-    float we = ld1(wp), ve = ld1(vp);
     if (HAS_G) st1(g + e, acc);
-    mc::sgd(acc, we, ve, hp);
-    st1(wp, we);
-    st1(vp, ve);
+    if (UPDATE) {
+        float* wp = w[t] + r;
+        float* vp = v[t] + r;
+        float we = ld1(wp), ve = ld1(vp);
+        mc::sgd(acc, we, ve, hp);
+        st1(wp, we);
+        st1(vp, ve);
+    }
 }
 
 // A whole tile that lies inside tensor t0, all operands sharing one alignment.  `rel` is the
@@ -107,7 +109,7 @@ __device__ __forceinline__ void one_element(const float* const* const* xs, int n
 // gp the matching position in the flat gradient.  SHIFTED: that boundary is not the tile's first
 // element, so gp is not 16-byte aligned (g is stored word by word) and the tile has one vector
 // less (n_vec); the few elements before and after the vectors are done by the caller.
-template <int P, int U, bool HAS_G, bool NT, bool SHIFTED>
+template <int P, int U, bool HAS_G, bool UPDATE, bool NT, bool SHIFTED>
 __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int np, int32_t t0, int64_t rel,
                                              float* wp, float* vp, float* gp, int n_vec,
                                              const mc::Hyper& hp) {
@@ -131,7 +133,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (on[u]) {
+            if (UPDATE && on[u]) {
                 wv[u] = load4<false>(wp + j[u]);
                 vv[u] = load4<false>(vp + j[u]);
             }
@@ -151,8 +153,10 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (on[u]) {
-                wv[u] = load4<false>(wp + j[u]);
-                vv[u] = load4<false>(vp + j[u]);
+                if (UPDATE) {
+                    wv[u] = load4<false>(wp + j[u]);
+                    vv[u] = load4<false>(vp + j[u]);
+                }
                 acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
             }
         }
@@ -184,18 +188,23 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
                 store4<NT>(gp + j[u], acc[u]);
             }
         }
-        mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
-        mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
-        mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
-        mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-        mc::store_state(wp + j[u], wv[u], hp.state_store_sc1);
-        mc::store_state(vp + j[u], vv[u], hp.state_store_sc1);
+        if (UPDATE) {
+            mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
+            mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
+            mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
+            mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
+            mc::store_state(wp + j[u], wv[u], hp.state_store_sc1);
+            mc::store_state(vp + j[u], vv[u], hp.state_store_sc1);
+        }
     }
 }
 
 // P > 0: compile-time number of terms; P == 0: run-time count in Prt.
-template <int P, int U, bool HAS_G, bool NT>
+// UPDATE: the SGD step follows the sum; otherwise only the sum is written to g (the colours of
+// which this rank is a leaf or inner node) and weights / momentum are never touched.
+template <int P, int U, bool HAS_G, bool UPDATE, bool NT>
 __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int Prt) {
+    static_assert(HAS_G || UPDATE, "a launch must produce something");
     constexpr int kTile = kThreads * 4 * U;
     const int np = P > 0 ? P : Prt;
     const mc::Hyper hp = mc::resolve(a.up);
@@ -219,25 +228,26 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
         // boundary (all zero for a CNN payload; equal and non-zero after an odd-sized tensor,
         // because frameworks align the tensors themselves), the tile runs on 128-bit accesses.
         const int64_t rel = base - t0_begin;
-        float* wp = a.w[t0] + rel;
-        float* vp = a.v[t0] + rel;
-        const int m = misalignment(wp);
-        bool same = misalignment(vp) == m;
-        for (int q = 0; q < np; ++q) same = same && misalignment(xs[q][t0] + rel) == m;
+        float* wp = UPDATE ? a.w[t0] + rel : nullptr;
+        float* vp = UPDATE ? a.v[t0] + rel : nullptr;
+        const int m = misalignment(xs[0][t0] + rel);
+        bool same = !UPDATE || (misalignment(wp) == m && misalignment(vp) == m);
+        for (int q = 1; q < np; ++q) same = same && misalignment(xs[q][t0] + rel) == m;
         if (same && m == 0) {
-            uniform_tile<P, U, HAS_G, NT, false>(xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
+            uniform_tile<P, U, HAS_G, UPDATE, NT, false>(xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
             return;
         }
         if (same) {
             const int head = 4 - m;               // elements up to the operands' 16-byte boundary
             const int n_vec = kTile / 4 - 1;      // whole vectors after it
-            uniform_tile<P, U, HAS_G, NT, true>(xs, np, t0, rel + head, wp + head, vp + head,
-                                                a.g + base + head, n_vec, hp);
+            uniform_tile<P, U, HAS_G, UPDATE, NT, true>(xs, np, t0, rel + head, UPDATE ? wp + head : nullptr,
+                                                        UPDATE ? vp + head : nullptr, a.g + base + head,
+                                                        n_vec, hp);
             // the `head` elements before the vectors and the `4 - head` after them
             if (threadIdx.x < 4) {
                 const int e = int(threadIdx.x) < head ? int(threadIdx.x)
                                                       : head + 4 * n_vec + (int(threadIdx.x) - head);
-                one_element<HAS_G>(xs, np, t0, rel + e, a.w, a.v, a.g, base + e, hp);
+                one_element<HAS_G, UPDATE>(xs, np, t0, rel + e, a.w, a.v, a.g, base + e, hp);
             }
             return;
         }
@@ -252,10 +262,8 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
         while (a.off[t + 1] <= i) ++t;  // ends: i < end <= N == off[n]
         const int64_t rel = i - a.off[t];
         bool vec = i + 4 <= end && i + 4 <= a.off[t + 1];
-        if (vec) {
-            vec = aligned16(a.w[t] + rel) && aligned16(a.v[t] + rel);
-            for (int q = 0; q < np && vec; ++q) vec = aligned16(xs[q][t] + rel);
-        }
+        if (vec && UPDATE) vec = aligned16(a.w[t] + rel) && aligned16(a.v[t] + rel);
+        for (int q = 0; q < np && vec; ++q) vec = aligned16(xs[q][t] + rel);
         if (vec) {
             float4 acc = load4<NT>(xs[0][t] + rel);
             for (int q = 1; q < np; ++q) {
@@ -265,58 +273,63 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
                 acc.z = acc.z + x.z;
                 acc.w = acc.w + x.w;
             }
-            float* wp = a.w[t] + rel;
-            float* vp = a.v[t] + rel;
-            float4 wq = load4<false>(wp);
-            float4 vq = load4<false>(vp);
             if (HAS_G) store4<false>(a.g + i, acc);
-            mc::sgd(acc.x, wq.x, vq.x, hp);
-            mc::sgd(acc.y, wq.y, vq.y, hp);
-            mc::sgd(acc.z, wq.z, vq.z, hp);
-            mc::sgd(acc.w, wq.w, vq.w, hp);
-            store4<false>(wp, wq);
-            store4<false>(vp, vq);
+            if (UPDATE) {
+                float* wp = a.w[t] + rel;
+                float* vp = a.v[t] + rel;
+                float4 wq = load4<false>(wp);
+                float4 vq = load4<false>(vp);
+                mc::sgd(acc.x, wq.x, vq.x, hp);
+                mc::sgd(acc.y, wq.y, vq.y, hp);
+                mc::sgd(acc.z, wq.z, vq.z, hp);
+                mc::sgd(acc.w, wq.w, vq.w, hp);
+                store4<false>(wp, wq);
+                store4<false>(vp, vq);
+            }
         } else {
             const int64_t stop = i + 4 < end ? i + 4 : end;
             for (int64_t e = i; e < stop; ++e) {
                 while (a.off[t + 1] <= e) ++t;
-                one_element<HAS_G>(xs, np, t, e - a.off[t], a.w, a.v, a.g, e, hp);
+                one_element<HAS_G, UPDATE>(xs, np, t, e - a.off[t], a.w, a.v, a.g, e, hp);
             }
         }
     }
 }
 
 template <int P, int U>
-void launch_variant(bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
+void launch_variant(bool update, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
     const dim3 grid(blocks), block(kThreads);
-#define MC_FUSED_LAUNCH(G, NT) hipLaunchKernelGGL((fused_step_kernel<P, U, G, NT>), grid, block, 0, s, a, Prt)
-    if (a.g) {
-        if (nt) MC_FUSED_LAUNCH(true, true); else MC_FUSED_LAUNCH(true, false);
+#define MC_FUSED_LAUNCH(G, UPD, NT) \
+    hipLaunchKernelGGL((fused_step_kernel<P, U, G, UPD, NT>), grid, block, 0, s, a, Prt)
+    if (!update) {
+        if (nt) MC_FUSED_LAUNCH(true, false, true); else MC_FUSED_LAUNCH(true, false, false);
+    } else if (a.g) {
+        if (nt) MC_FUSED_LAUNCH(true, true, true); else MC_FUSED_LAUNCH(true, true, false);
     } else {
-        if (nt) MC_FUSED_LAUNCH(false, true); else MC_FUSED_LAUNCH(false, false);
+        if (nt) MC_FUSED_LAUNCH(false, true, true); else MC_FUSED_LAUNCH(false, true, false);
     }
 #undef MC_FUSED_LAUNCH
 }
 
 template <int P>
-void launch_unroll(int unroll, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
+void launch_unroll(int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
     if (unroll == 1)
-        launch_variant<P, 1>(nt, blocks, s, a, Prt);
+        launch_variant<P, 1>(update, nt, blocks, s, a, Prt);
     else
-        launch_variant<P, 2>(nt, blocks, s, a, Prt);
+        launch_variant<P, 2>(update, nt, blocks, s, a, Prt);
 }
 
-void launch(int P, int unroll, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a) {
+void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a) {
     switch (P) {
-        case 1: launch_unroll<1>(unroll, nt, blocks, s, a, P); break;
-        case 2: launch_unroll<2>(unroll, nt, blocks, s, a, P); break;
-        case 3: launch_unroll<3>(unroll, nt, blocks, s, a, P); break;
-        case 4: launch_unroll<4>(unroll, nt, blocks, s, a, P); break;
-        case 5: launch_unroll<5>(unroll, nt, blocks, s, a, P); break;
-        case 6: launch_unroll<6>(unroll, nt, blocks, s, a, P); break;
-        case 7: launch_unroll<7>(unroll, nt, blocks, s, a, P); break;
-        case 8: launch_unroll<8>(unroll, nt, blocks, s, a, P); break;
-        default: launch_unroll<0>(unroll, nt, blocks, s, a, P); break;
+        case 1: launch_unroll<1>(unroll, update, nt, blocks, s, a, P); break;
+        case 2: launch_unroll<2>(unroll, update, nt, blocks, s, a, P); break;
+        case 3: launch_unroll<3>(unroll, update, nt, blocks, s, a, P); break;
+        case 4: launch_unroll<4>(unroll, update, nt, blocks, s, a, P); break;
+        case 5: launch_unroll<5>(unroll, update, nt, blocks, s, a, P); break;
+        case 6: launch_unroll<6>(unroll, update, nt, blocks, s, a, P); break;
+        case 7: launch_unroll<7>(unroll, update, nt, blocks, s, a, P); break;
+        case 8: launch_unroll<8>(unroll, update, nt, blocks, s, a, P); break;
+        default: launch_unroll<0>(unroll, update, nt, blocks, s, a, P); break;
     }
 }
 
@@ -406,11 +419,13 @@ int mc_tensor_set_destroy(mc_tensor_set* S) {
 }
 
 static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
-                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
-                     const mc::UpdateParams& up, void* stream) {
-    if (!L || !contrib || !weights || !momentum || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+                          const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
+                          const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                          const mc::UpdateParams& up, void* stream) {
+    if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if ((n_terms == nullptr) != (do_update == nullptr)) return MC_ERR_INVALID_ARG;
     if (up.hyper && !mc::aligned(up.hyper, 4)) return MC_ERR_ALIGN;
-    if (weights->layout != L || momentum->layout != L) return MC_ERR_INVALID_ARG;
+    if ((weights && weights->layout != L) || (momentum && momentum->layout != L)) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
         if (!contrib[p] || contrib[p]->layout != L) return MC_ERR_INVALID_ARG;
     if (order) {
@@ -423,23 +438,31 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             }
         }
     }
-    if (L->N == 0) return MC_OK;
+    bool any_update = false, any_sum_only = false;
+    for (int32_t c = 0; c < L->k; ++c) {
+        if (n_terms && (n_terms[c] < 0 || n_terms[c] > P)) return MC_ERR_INVALID_ARG;
+        if ((n_terms && n_terms[c] == 0) || L->bounds[c + 1] == L->bounds[c]) continue;
+        if (!do_update || do_update[c]) any_update = true; else any_sum_only = true;
+    }
+    if (!any_update && !any_sum_only) return MC_OK;
+    if (any_update && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
+    if (any_sum_only && !grad_out) return MC_ERR_INVALID_ARG;
     if (grad_out && !mc::aligned(grad_out, 16)) return MC_ERR_ALIGN;
 
     // Nothing written (weights, momentum, grad_out) may overlap anything else of the call.
     // A contribution may appear twice (it is only read).
     const mc_tensor_set* written[2] = {weights, momentum};
-    if (spans_overlap(weights->spans, momentum->spans)) return MC_ERR_OVERLAP;
+    if (weights && momentum && spans_overlap(weights->spans, momentum->spans)) return MC_ERR_OVERLAP;
     std::vector<std::pair<uintptr_t, uintptr_t>> gspan;
     if (grad_out) {
         const uintptr_t b = reinterpret_cast<uintptr_t>(grad_out);
         gspan.emplace_back(b, b + uintptr_t(L->N) * 4);
         for (const mc_tensor_set* wset : written)
-            if (spans_overlap(wset->spans, gspan)) return MC_ERR_OVERLAP;
+            if (wset && spans_overlap(wset->spans, gspan)) return MC_ERR_OVERLAP;
     }
     for (int32_t p = 0; p < P; ++p) {
         for (const mc_tensor_set* wset : written)
-            if (spans_overlap(contrib[p]->spans, wset->spans)) return MC_ERR_OVERLAP;
+            if (wset && spans_overlap(contrib[p]->spans, wset->spans)) return MC_ERR_OVERLAP;
         if (grad_out && spans_overlap(contrib[p]->spans, gspan)) return MC_ERR_OVERLAP;
     }
 
@@ -448,65 +471,87 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     if (rc != MC_OK) return rc;
     int dev = -1;
     MC_HIP_TRY(hipGetDevice(&dev));
-    if (weights->device != dev || momentum->device != dev) return MC_ERR_INVALID_ARG;
+    if ((weights && weights->device != dev) || (momentum && momentum->device != dev)) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
         if (contrib[p]->device != dev) return MC_ERR_INVALID_ARG;
 
     const int unroll = mc::unroll_for(L->N);
     const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
     const int64_t tile = int64_t(kThreads) * 4 * unroll;
-    const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / P);
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     FusedArgs a;
-    a.w = reinterpret_cast<float* const*>(weights->d_ptrs);
-    a.v = reinterpret_cast<float* const*>(momentum->d_ptrs);
+    a.w = weights ? reinterpret_cast<float* const*>(weights->d_ptrs) : nullptr;
+    a.v = momentum ? reinterpret_cast<float* const*>(momentum->d_ptrs) : nullptr;
     a.g = static_cast<float*>(grad_out);
     a.off = dt->off;
     a.first_tensor = dt->tile_first;
     a.up = up;
-    int32_t c = 0;
-    while (c < L->k) {
-        int ns = 0;
-        int64_t blocks = 0;
-        a.first_block[0] = 0;
-        for (; c < L->k && ns < segs_per_launch; ++c) {
-            const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
-            if (hi == lo) continue;
-            const int64_t nblk = (hi - lo + tile - 1) / tile;
-            if (blocks + nblk > 0x7fffffff) {
-                if (ns == 0) return MC_ERR_INVALID_ARG;
-                break;
-            }
-            a.lo[ns] = lo;
-            a.hi[ns] = hi;
-            for (int32_t q = 0; q < P; ++q) {
-                const int32_t src = order ? order[size_t(c) * P + q] : q;
-                a.x[ns * P + q] = reinterpret_cast<const float* const*>(contrib[src]->d_ptrs);
-            }
-            blocks += nblk;
-            a.first_block[ns + 1] = int32_t(blocks);
-            ++ns;
+
+    // Colours that add the same number of terms and agree on updating share launches (at most two
+    // such classes for a real rank; one for the uniform call).  `done` marks colours launched.
+    std::vector<uint8_t> done(size_t(L->k), 0);
+    for (int32_t c0 = 0; c0 < L->k; ++c0) {
+        if (done[c0]) continue;
+        const int32_t cnt = n_terms ? n_terms[c0] : P;
+        const bool upd = do_update ? do_update[c0] != 0 : true;
+        if (cnt == 0 || L->bounds[c0 + 1] == L->bounds[c0]) {
+            done[c0] = 1;
+            continue;
         }
-        if (ns == 0) break;
-        for (int i = ns * P; i < kPtrSlots; ++i) a.x[i] = nullptr;
-        for (int i = ns; i < kMaxSegs; ++i) {
-            a.lo[i] = a.hi[i] = 0;
-            a.first_block[i + 1] = a.first_block[ns];
+        const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / cnt);
+        int32_t c = c0;
+        while (c < L->k) {
+            int ns = 0;
+            int64_t blocks = 0;
+            a.first_block[0] = 0;
+            for (; c < L->k && ns < segs_per_launch; ++c) {
+                if (done[c]) continue;
+                const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
+                const int32_t cc = n_terms ? n_terms[c] : P;
+                const bool cu = do_update ? do_update[c] != 0 : true;
+                if (cc == 0 || hi == lo) {
+                    done[c] = 1;
+                    continue;
+                }
+                if (cc != cnt || cu != upd) continue;  // another class: a later pass takes it
+                const int64_t nblk = (hi - lo + tile - 1) / tile;
+                if (blocks + nblk > 0x7fffffff) {
+                    if (ns == 0) return MC_ERR_INVALID_ARG;
+                    break;
+                }
+                a.lo[ns] = lo;
+                a.hi[ns] = hi;
+                for (int32_t q = 0; q < cnt; ++q) {
+                    const int32_t src = order ? order[size_t(c) * P + q] : q;
+                    a.x[ns * cnt + q] = reinterpret_cast<const float* const*>(contrib[src]->d_ptrs);
+                }
+                blocks += nblk;
+                a.first_block[ns + 1] = int32_t(blocks);
+                done[c] = 1;
+                ++ns;
+            }
+            if (ns == 0) break;
+            for (int i = ns * cnt; i < kPtrSlots; ++i) a.x[i] = nullptr;
+            for (int i = ns; i < kMaxSegs; ++i) {
+                a.lo[i] = a.hi[i] = 0;
+                a.first_block[i + 1] = a.first_block[ns];
+            }
+            a.n_segs = ns;
+            launch(cnt, unroll, upd, nt, unsigned(blocks), s, a);
+            MC_HIP_TRY(hipGetLastError());
         }
-        a.n_segs = ns;
-        launch(P, unroll, nt, unsigned(blocks), s, a);
-        MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
 }
 
 // No C++ exception may cross the C boundary.
 static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
-                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
+                     const mc_tensor_set* weights, const mc_tensor_set* momentum,
                      const mc::UpdateParams& up, void* stream) {
     try {
-        return fused_run_impl(L, contrib, P, order, grad_out, weights, momentum, up, stream);
+        return fused_run_impl(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up, stream);
     } catch (const std::bad_alloc&) {
         return MC_ERR_ALLOC;
     }
@@ -522,16 +567,18 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
     up.hyper = nullptr;
     up.nesterov = 0;
     up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
-    return fused_run(L, contrib, P, order, grad_out, weights, momentum, up, stream);
+    if (!weights || !momentum) return MC_ERR_INVALID_ARG;
+    return fused_run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, up, stream);
 }
 
 int mc_fused_step_ex(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
-                     void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
+                     const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
+                     const mc_tensor_set* weights, const mc_tensor_set* momentum,
                      const mc_update_spec* spec, void* stream) {
     mc::UpdateParams up;
     const int rc = mc::update_params(spec, &up);
     if (rc != MC_OK) return rc;
-    return fused_run(L, contrib, P, order, grad_out, weights, momentum, up, stream);
+    return fused_run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up, stream);
 }
 
 }  // extern "C"

@@ -62,7 +62,8 @@ SIGNATURES = {
     "mc_reduce_update_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
                                            ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp, _vp,
                                            ctypes.c_int64, ctypes.c_int64, _vp]),
-    "mc_fused_step_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp, _vp, _vp]),
+    "mc_fused_step_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
+                                        ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp, _vp, _vp]),
     "mc_hyper_write": (ctypes.c_int, [_vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
     "mc_lr_schedule": (ctypes.c_int, [ctypes.c_float, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                       ctypes.c_float, ctypes.c_float, ctypes.POINTER(ctypes.c_float)]),
@@ -374,10 +375,18 @@ def reduce_update_ex(layout: Layout, contrib_ptrs, order, grad_out_ptr, weights_
 
 
 def fused_step_ex(layout: Layout, contrib_sets, order, grad_out_ptr, weights: "TensorSet",
-                  momentum: "TensorSet", spec: UpdateSpec, stream: int = 0) -> None:
+                  momentum: "TensorSet", spec: UpdateSpec, stream: int = 0, n_terms=None,
+                  do_update=None) -> None:
     tab = contrib_sets if isinstance(contrib_sets, ctypes.Array) else set_table(contrib_sets)
     _o, optr = _order_ptr(order, layout.k, tab.count)
-    _check(lib.mc_fused_step_ex(layout.handle, tab, tab.count, optr, grad_out_ptr,
+    ntp = dup = None
+    if n_terms is not None or do_update is not None:
+        nt = np.ascontiguousarray(n_terms, dtype=np.int32)
+        du = np.ascontiguousarray(do_update, dtype=np.uint8)
+        if nt.size != layout.k or du.size != layout.k:
+            raise ValueError("n_terms and do_update must hold k_colours entries")
+        ntp, dup = nt.ctypes.data_as(_i32p), du.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    _check(lib.mc_fused_step_ex(layout.handle, tab, tab.count, optr, ntp, dup, grad_out_ptr,
                                 weights.handle if weights is not None else None,
                                 momentum.handle if momentum is not None else None,
                                 ctypes.byref(spec) if spec is not None else None, stream or None),

@@ -122,3 +122,65 @@ def test_whole_allreduce_on_gpu_matches_oracle_and_plain_sum(n_nodes, k, m):
     for c in range(k):
         lo, hi = int(O.bounds[c]), int(O.bounds[c + 1])
         gh.assert_bits(g1[lo:hi], sim.tree_order_sum(parents_ref[c], m, local, lo, hi), f"tree order colour {c}")
+
+
+def _fused_call(L, O, sizes):
+    """The same adapter through mc_fused_step_ex: every contribution, the weights and the
+    momentum live in separate per-layer tensors (odd layers misaligned), g is flat."""
+    def call(contrib, n_terms, do_update, g, w, v, lr, mu, wd, order):
+        s = gh.stream_handle()
+        mis = [0, 0, 1]
+        dev_x = [gh.place_tensors(oracle.unpack(O, np.ascontiguousarray(x)), mis)[0] for x in contrib]
+        sets = [mc.TensorSet(L, gh.ptrs(d)) for d in dev_x]
+        gd = gh.to_dev(g)
+        wset = vset = None
+        if w is not None:
+            dev_w, _ = gh.place_tensors(oracle.unpack(O, w), mis)
+            dev_v, _ = gh.place_tensors(oracle.unpack(O, v), mis)
+            wset, vset = mc.TensorSet(L, gh.ptrs(dev_w)), mc.TensorSet(L, gh.ptrs(dev_v))
+        mc.fused_step_ex(L, sets, order, gd.data_ptr(), wset, vset, mc.update_spec(lr, mu, wd), s,
+                         n_terms=n_terms, do_update=do_update)
+        torch.cuda.synchronize()
+        g[:] = gd.cpu().numpy()
+        if w is not None:
+            w[:] = oracle.pack(O, [t.cpu().numpy() for t in dev_w])
+            v[:] = oracle.pack(O, [t.cpu().numpy() for t in dev_v])
+    call.bounds = L.colour_bounds()
+    return call
+
+
+@pytest.mark.parametrize("sizes", [[9000, 32, 2500], [9001, 33, 2503]], ids=["aligned", "odd"])
+def test_fused_roles_match_oracle_and_compose_to_an_allreduce(sizes):
+    n_nodes, k, m = 8, 4, 2
+    L = mc.Layout(sizes, k)
+    O = oracle.Layout(sizes, k)
+    N = L.N
+    rng = np.random.Generator(np.random.PCG64(5))
+    # one mixed-role call against the oracle
+    P = 5
+    xs = [rng.standard_normal(N, dtype=np.float32) * np.float32(1e-3) for _ in range(P)]
+    w0 = rng.standard_normal(N, dtype=np.float32) * np.float32(0.05)
+    v0 = rng.standard_normal(N, dtype=np.float32) * np.float32(0.01)
+    n_terms, do_update = [P, 0, 2, 3], [1, 1, 0, 1]
+    order = wl.random_order(k, P, seed=1)
+    g1, w1, v1 = np.full(N, 7.0, np.float32), w0.copy(), v0.copy()
+    _fused_call(L, O, sizes)(xs, n_terms, do_update, g1, w1, v1, 0.1, 0.9, 1e-4, order)
+    g2, w2, v2 = np.full(N, 7.0, np.float32), w0.copy(), v0.copy()
+    oracle.reduce_update_roles(O, xs, n_terms, do_update, g2, w2, v2, 0.1, 0.9, 1e-4, order=order)
+    gh.assert_bits(g1, g2, "fused roles g")
+    gh.assert_bits(w1, w2, "fused roles w")
+    gh.assert_bits(v1, v2, "fused roles v")
+    # sum-only call needs no weights
+    g3 = np.zeros(N, np.float32)
+    _fused_call(L, O, sizes)(xs, [2, 2, 2, 2], [0, 0, 0, 0], g3, None, None, 0.1, 0.9, 1e-4, None)
+    gh.assert_bits(g3, xs[0] + xs[1], "fused sum only")
+    # the whole Allreduce composed from fused role calls
+    parents = mc.colour_trees(n_nodes, k).tolist()
+    local = [[rng.standard_normal(N, dtype=np.float32) * np.float32(1e-3) for _ in range(m)] for _ in range(n_nodes)]
+    print(f"fused allreduce sim sizes={sizes}", flush=True)
+    ga, wa, va = sim.simulate(_fused_call(L, O, sizes), parents, m, local, w0, np.zeros(N, np.float32), N, k, 0.1, 0.9, 1e-4)
+    gb, wb, vb = sim.simulate(_oracle_call(O), parents, m, local, w0, np.zeros(N, np.float32), N, k, 0.1, 0.9, 1e-4)
+    gh.assert_bits(ga, gb, "g_total")
+    for node in range(n_nodes):
+        gh.assert_bits(wa[node], wb[node], f"w node {node}")
+        gh.assert_bits(va[node], vb[node], f"v node {node}")

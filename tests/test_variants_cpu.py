@@ -145,7 +145,7 @@ def test_library_schedule_and_spec_reject():
     assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(0.1, 0.9, 0.0), elem_begin=100) == mc.ERR_INVALID_ARG
     assert code(mc.hyper_write, None, 0.1, 0.9, 0.0) == mc.ERR_INVALID_ARG
     assert code(mc.hyper_write, B + 1, 0.1, 0.9, 0.0) == mc.ERR_ALIGN
-    assert mc.lib.mc_fused_step_ex(L.handle, None, 1, None, None, None, None, None, None) == mc.ERR_INVALID_ARG
+    assert mc.lib.mc_fused_step_ex(L.handle, None, 1, None, None, None, None, None, None, None, None) == mc.ERR_INVALID_ARG
 
 
 def test_planted_mistakes_in_the_nesterov_step_are_caught():
