@@ -211,6 +211,11 @@ int mc_reduce_update_range(const mc_layout* L, const void* const* contrib, int32
 typedef struct mc_tensor_set mc_tensor_set;   /* opaque */
 int mc_tensor_set_create(mc_layout* L, const void* const* tensors, mc_tensor_set** out);
 int mc_tensor_set_destroy(mc_tensor_set* S);
+/* mc_pack / mc_unpack with the tensor pointers taken from a set: one launch whatever the number of
+ * tensors (the pointer-array forms need one launch per 256 tensors).  Same copies, same errors;
+ * MC_ERR_INVALID_ARG also for a set of another layout or device. */
+int mc_pack_set(mc_layout* L, const mc_tensor_set* tensors, void* flat, void* stream);
+int mc_unpack_set(mc_layout* L, const void* flat, const mc_tensor_set* tensors, void* stream);
 int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
                   void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
                   float lr, float mu, float wd, void* stream);

@@ -22,14 +22,6 @@
 
 #pragma clang fp contract(off)
 
-struct mc_tensor_set {
-    const mc_layout* layout = nullptr;
-    int device = -1;
-    void** d_ptrs = nullptr;                            // device: n pointers
-    std::vector<const void*> ptrs;                      // host copy
-    std::vector<std::pair<uintptr_t, uintptr_t>> spans; // non-empty tensors' [begin, end), sorted
-};
-
 namespace {
 
 constexpr int kThreads = 256;

@@ -5,6 +5,7 @@
 
 #include <cstdint>
 #include <mutex>
+#include <utility>
 #include <vector>
 
 #include "mc.h"
@@ -42,6 +43,15 @@ struct mc_layout {
     std::vector<int32_t> tile_first;  // ceil(N / kLookupElems) + 1
     std::mutex mu;                    // guards dev[] during prepare / destroy
     mc::DeviceTables dev[mc::kMaxDevices];
+};
+
+// The device-resident list of one tensor pointer per layer of a layout.
+struct mc_tensor_set {
+    const mc_layout* layout = nullptr;
+    int device = -1;
+    void** d_ptrs = nullptr;                             // device: n pointers
+    std::vector<const void*> ptrs;                       // host copy
+    std::vector<std::pair<uintptr_t, uintptr_t>> spans;  // non-empty tensors' [begin, end), sorted
 };
 
 namespace mc {

@@ -7,7 +7,9 @@
 // 16-byte aligned, like the CNN payloads), and four 32-bit accesses otherwise.
 //
 // Device pointers of the tensors travel in the kernel-argument block (no staging copy, no
-// synchronisation); a layout with more tensors than fit is processed in several launches.
+// synchronisation); a layout with more tensors than fit is processed in several launches.  The
+// `_set` forms read the pointers from a tensor set's device table instead: one launch whatever
+// the number of tensors.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -59,8 +61,8 @@ __device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
 // V: 16-byte vectors per thread; a workgroup covers a tile of kThreads * 4 * V flat elements.
 template <bool UNPACK, bool NT_T, bool NT_F, int V>
 __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
-    PtrBatch ptrs, const int64_t* __restrict__ off, const int32_t* __restrict__ tile_first,
-    uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0) {
+    PtrBatch ptrs, void* const* __restrict__ table, const int64_t* __restrict__ off,
+    const int32_t* __restrict__ tile_first, uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0) {
     constexpr int64_t kTileElems = int64_t(kThreads) * 4 * V;
     static_assert(kTileElems % mc::kLookupElems == 0, "tiles start on lookup entries");
     const int64_t tile = tile0 + blockIdx.x;
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
 
         const bool one_tensor = i >= lo && i + 4 <= off[t + 1];
         if (one_tensor) {
-            uint32_t* src = static_cast<uint32_t*>(ptrs.p[t - t0]) + (i - off[t]);
+            uint32_t* src = static_cast<uint32_t*>(table ? table[t] : ptrs.p[t - t0]) + (i - off[t]);
             if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
                 if (UNPACK)
                     st4<NT_T>(src, ld4<NT_F>(flat + i));
@@ -107,13 +109,49 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
             const int64_t idx = i + e;
             if (idx < lo || idx >= hi) continue;
             while (off[t + 1] <= idx) ++t;
-            uint32_t* elem = static_cast<uint32_t*>(ptrs.p[t - t0]) + (idx - off[t]);
+            uint32_t* elem = static_cast<uint32_t*>(table ? table[t] : ptrs.p[t - t0]) + (idx - off[t]);
             if (UNPACK)
                 *elem = flat[idx];
             else
                 flat[idx] = *elem;
         }
     }
+}
+
+// One launch over tensors [t0, t1): pointers from `batch` (kernel arguments) or, if given, from
+// the device table of a tensor set.
+template <bool UNPACK>
+int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch& batch, void* const* table,
+                 void* flat, int32_t t0, int32_t t1, hipStream_t s) {
+    const int64_t lo = L->off[t0], hi = L->off[t1];
+    if (lo == hi) return MC_OK;
+    const int nt = mc::option(MC_OPT_PACK_NONTEMPORAL);
+    // Small payloads use the finer tile so that the grid still fills the chip evenly.
+    const int vec = L->N / mc::kPackTileElems >= 8192 ? 2 : 1;
+    const int64_t tile_elems = int64_t(kThreads) * 4 * vec;
+    const int64_t tile0 = lo / tile_elems;
+    const int64_t tile_end = (hi + tile_elems - 1) / tile_elems;
+    if (tile_end - tile0 > 0x7fffffff) return MC_ERR_INVALID_ARG;
+    const dim3 grid(unsigned(tile_end - tile0)), block(kThreads);
+    uint32_t* f = static_cast<uint32_t*>(flat);
+#define MC_GS_LAUNCH(NT_T, NT_F)                                                                       \
+    do {                                                                                               \
+        if (vec == 2)                                                                                  \
+            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, 0, s, batch, \
+                               table, dt->off, dt->tile_first, f, t0, t1, tile0);                      \
+        else                                                                                           \
+            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, 0, s, batch, \
+                               table, dt->off, dt->tile_first, f, t0, t1, tile0);                      \
+    } while (0)
+    switch (nt & 3) {
+        case 0: MC_GS_LAUNCH(false, false); break;
+        case 1: MC_GS_LAUNCH(true, false); break;
+        case 2: MC_GS_LAUNCH(false, true); break;
+        default: MC_GS_LAUNCH(true, true); break;
+    }
+#undef MC_GS_LAUNCH
+    MC_HIP_TRY(hipGetLastError());
+    return MC_OK;
 }
 
 template <bool UNPACK>
@@ -135,40 +173,35 @@ int run(mc_layout* L, void* const* tensors, void* flat, void* stream) {
     if (rc != MC_OK) return rc;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int nt = mc::option(MC_OPT_PACK_NONTEMPORAL);
     for (int32_t t0 = 0; t0 < L->n; t0 += mc::kPackMaxPtrs) {
         const int32_t t1 = std::min<int32_t>(L->n, t0 + mc::kPackMaxPtrs);
-        const int64_t lo = L->off[t0], hi = L->off[t1];
-        if (lo == hi) continue;
         PtrBatch batch;
         for (int32_t t = t0; t < t1; ++t) batch.p[t - t0] = tensors[t];
         for (int32_t t = t1 - t0; t < mc::kPackMaxPtrs; ++t) batch.p[t] = nullptr;
-        // Small payloads use the finer tile so that the grid still fills the chip evenly.
-        const int vec = L->N / mc::kPackTileElems >= 8192 ? 2 : 1;
-        const int64_t tile_elems = int64_t(kThreads) * 4 * vec;
-        const int64_t tile0 = lo / tile_elems;
-        const int64_t tile_end = (hi + tile_elems - 1) / tile_elems;
-        const dim3 grid(unsigned(tile_end - tile0)), block(kThreads);
-        uint32_t* f = static_cast<uint32_t*>(flat);
-#define MC_GS_LAUNCH(NT_T, NT_F)                                                                       \
-    do {                                                                                               \
-        if (vec == 2)                                                                                  \
-            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, 0, s, batch, \
-                               dt->off, dt->tile_first, f, t0, t1, tile0);                             \
-        else                                                                                           \
-            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, 0, s, batch, \
-                               dt->off, dt->tile_first, f, t0, t1, tile0);                             \
-    } while (0)
-        switch (nt & 3) {
-            case 0: MC_GS_LAUNCH(false, false); break;
-            case 1: MC_GS_LAUNCH(true, false); break;
-            case 2: MC_GS_LAUNCH(false, true); break;
-            default: MC_GS_LAUNCH(true, true); break;
-        }
-#undef MC_GS_LAUNCH
-        MC_HIP_TRY(hipGetLastError());
+        const int lrc = launch_range<UNPACK>(L, dt, batch, nullptr, flat, t0, t1, s);
+        if (lrc != MC_OK) return lrc;
     }
     return MC_OK;
+}
+
+template <bool UNPACK>
+int run_set(mc_layout* L, const mc_tensor_set* S, void* flat, void* stream) {
+    if (!L || !S || S->layout != L) return MC_ERR_INVALID_ARG;
+    if (L->N == 0) return MC_OK;
+    if (!flat) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(flat, 16)) return MC_ERR_ALIGN;
+    const uintptr_t fb = reinterpret_cast<uintptr_t>(flat), fe = fb + uintptr_t(L->N) * 4;
+    for (const auto& span : S->spans)
+        if (span.first < fe && fb < span.second) return MC_ERR_OVERLAP;
+    const mc::DeviceTables* dt = nullptr;
+    const int rc = mc::device_tables(L, &dt);
+    if (rc != MC_OK) return rc;
+    int dev = -1;
+    MC_HIP_TRY(hipGetDevice(&dev));
+    if (S->device != dev) return MC_ERR_INVALID_ARG;
+    PtrBatch none;
+    for (int i = 0; i < mc::kPackMaxPtrs; ++i) none.p[i] = nullptr;
+    return launch_range<UNPACK>(L, dt, none, S->d_ptrs, flat, 0, L->n, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -243,6 +276,14 @@ int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream) 
 
 int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream) {
     return run<true>(L, tensors, const_cast<void*>(flat), stream);
+}
+
+int mc_pack_set(mc_layout* L, const mc_tensor_set* tensors, void* flat, void* stream) {
+    return run_set<false>(L, tensors, flat, stream);
+}
+
+int mc_unpack_set(mc_layout* L, const void* flat, const mc_tensor_set* tensors, void* stream) {
+    return run_set<true>(L, tensors, const_cast<void*>(flat), stream);
 }
 
 }  // extern "C"

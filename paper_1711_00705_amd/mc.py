@@ -57,6 +57,8 @@ SIGNATURES = {
                                               ctypes.c_int64, ctypes.c_int64, _vp]),
     "mc_tensor_set_create": (ctypes.c_int, [_vp, _vpp, ctypes.POINTER(_vp)]),
     "mc_tensor_set_destroy": (ctypes.c_int, [_vp]),
+    "mc_pack_set": (ctypes.c_int, [_vp, _vp, _vp, _vp]),
+    "mc_unpack_set": (ctypes.c_int, [_vp, _vp, _vp, _vp]),
     "mc_fused_step": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
                                      ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
     "mc_reduce_update_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
@@ -308,6 +310,16 @@ class TensorSet:
 
 def tensor_set_create(layout: Layout, tensor_ptrs) -> TensorSet:
     return TensorSet(layout, tensor_ptrs)
+
+
+def pack_set(layout: Layout, tensors: TensorSet, flat_ptr: Optional[int], stream: int = 0) -> None:
+    _check(lib.mc_pack_set(layout.handle, tensors.handle if tensors is not None else None, flat_ptr,
+                           stream or None), "mc_pack_set")
+
+
+def unpack_set(layout: Layout, flat_ptr: Optional[int], tensors: TensorSet, stream: int = 0) -> None:
+    _check(lib.mc_unpack_set(layout.handle, flat_ptr, tensors.handle if tensors is not None else None,
+                             stream or None), "mc_unpack_set")
 
 
 def set_table(sets):

@@ -22,7 +22,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
-    assert len(names) >= 26
+    assert len(names) >= 28
     raw = ctypes.CDLL(mc.LIBRARY_PATH)
     for n in names:
         assert hasattr(raw, n), f"{n} declared in mc.h but not exported"
@@ -230,6 +230,8 @@ def test_tensor_set_rejects_before_touching_the_gpu():
     assert f(L.handle, mc.ptr_table([B + 1, None, B + 8192]), ctypes.byref(out)) == mc.ERR_ALIGN
     assert f(L.handle, mc.ptr_table([B, None, B + 3996]), ctypes.byref(out)) == mc.ERR_OVERLAP
     assert mc.lib.mc_tensor_set_destroy(None) == mc.OK
+    assert mc.lib.mc_pack_set(L.handle, None, B, None) == mc.ERR_INVALID_ARG
+    assert mc.lib.mc_unpack_set(None, B, None, None) == mc.ERR_INVALID_ARG
     assert mc.lib.mc_fused_step(L.handle, None, 1, None, None, None, None, 0., 0., 0., None) == mc.ERR_INVALID_ARG
 
 

@@ -322,3 +322,48 @@ def test_copy_yardstick_copies():
     h = buf.cpu().numpy().view(np.uint32)
     assert np.all(h[:64] == 0xFFFFFFFF) and np.all(h[64 + n:] == 0xFFFFFFFF)
     assert np.array_equal(h[64:64 + n], np.arange(n, dtype=np.uint32))
+
+
+def test_pack_and_unpack_through_tensor_sets_with_thousands_of_tensors():
+    """The set forms take the pointers from a device table: one launch for 5000 tensors (the
+    pointer-array forms need twenty), same words either way."""
+    rng = np.random.Generator(np.random.PCG64(31))
+    sizes = [int(s) for s in rng.choice([0, 1, 3, 4, 16, 17, 64, 100, 255, 1024], size=5000)]
+    L = mc.Layout(sizes, 7)
+    O = oracle.Layout(sizes, 7)
+    N = L.N
+    host = [rng.integers(0, 2 ** 32, size=s, dtype=np.uint64).astype(np.uint32).view(np.float32) for s in sizes]
+    for mis in ([0], [1, 0, 3, 2, 0, 0, 1]):
+        dts, _ = gh.place_tensors(host, mis)
+        tset = mc.TensorSet(L, gh.ptrs(dts))
+        G = 64
+        buf = gh.dev_empty(N + 2 * G)
+        flat = buf[G:G + N]
+        mc.pack_set(L, tset, flat.data_ptr(), gh.stream_handle())
+        flat2 = gh.dev_empty(N)
+        mc.pack(L, gh.ptrs(dts), flat2.data_ptr(), gh.stream_handle())
+        torch.cuda.synchronize()
+        h = buf.cpu().numpy().view(np.uint32)
+        assert np.all(h[:G] == 0xFFFFFFFF) and np.all(h[G + N:] == 0xFFFFFFFF)
+        want = oracle.pack(O, host)
+        gh.assert_bits(h[G:G + N].view(np.float32), want, "pack_set")
+        gh.assert_bits(flat2[:N].cpu().numpy(), want, "pack (20 launches)")
+        outs, arena = gh.place_tensors([np.zeros(s, np.float32) for s in sizes], mis)
+        oset = mc.TensorSet(L, gh.ptrs(outs))
+        before = arena.cpu().numpy().view(np.uint32).copy()
+        mc.unpack_set(L, flat.data_ptr(), oset, gh.stream_handle())
+        torch.cuda.synchronize()
+        after = arena.cpu().numpy().view(np.uint32)
+        touched = np.zeros(after.size, bool)
+        for o, t in zip(outs, host):
+            lo = (o.data_ptr() - arena.data_ptr()) // 4
+            touched[lo:lo + t.size] = True
+            gh.assert_bits(o.cpu().numpy(), t, "unpack_set")
+        assert np.array_equal(after[~touched], before[~touched]), "unpack_set wrote outside its tensors"
+        # a set must not overlap the flat buffer it is packed into
+        alias = mc.TensorSet(L, [flat.data_ptr() + 4 * int(o) for o in L.tensor_offsets()[:-1]])
+        with pytest.raises(mc.McError) as e:
+            mc.pack_set(L, alias, flat.data_ptr(), gh.stream_handle())
+        assert e.value.code == mc.ERR_OVERLAP
+        for s_ in (tset, oset, alias):
+            s_.destroy()
