@@ -228,3 +228,40 @@ def test_googlenet_fused_steps_carry_state():
                 gh.assert_bits(a.cpu().numpy(), b, f"w after step {step + 1}")
             for a, b in zip(v_layers, oracle.unpack(O, vr)):
                 gh.assert_bits(a.cpu().numpy(), b, f"v after step {step + 1}")
+
+
+def test_checkpoint_and_resume_give_identical_bits():
+    """The state of training is exactly (weights, momentum): three steps in a row equal two
+    steps, a download of the state, a fresh set of buffers, and the third step."""
+    sizes = ALIGNED_SIZES
+    k, P = 4, 4
+    L = mc.Layout(sizes, k)
+    order = wl.rotation_order(k, P)
+    s = gh.stream_handle()
+    contribs = [[wl.contribution_tensors(sizes, p, step=t) for p in range(P)] for t in range(3)]
+
+    def fresh_state(w_host, v_host):
+        dw, _ = gh.place_tensors(w_host)
+        dv, _ = gh.place_tensors(v_host)
+        return dw, dv, mc.TensorSet(L, gh.ptrs(dw)), mc.TensorSet(L, gh.ptrs(dv))
+
+    def run_steps(dw, dv, wset, vset, steps):
+        g = gh.dev_empty(L.N)
+        for t in steps:
+            dev = [gh.place_tensors(c)[0] for c in contribs[t]]
+            sets = [mc.TensorSet(L, gh.ptrs(d)) for d in dev]
+            mc.fused_step(L, sets, order, g.data_ptr(), wset, vset, 0.1, 0.9, 1e-4, s)
+            torch.cuda.synchronize()
+            for st in sets:
+                st.destroy()
+        return [t.cpu().numpy() for t in dw], [t.cpu().numpy() for t in dv], g.cpu().numpy()
+
+    w0, v0 = wl.weight_tensors(sizes), wl.zero_tensors(sizes)
+    straight = run_steps(*fresh_state(w0, v0), steps=(0, 1, 2))
+    w2, v2, _ = run_steps(*fresh_state(w0, v0), steps=(0, 1))          # ... checkpoint here
+    resumed = run_steps(*fresh_state(w2, v2), steps=(2,))               # ... resume from it
+    for a, b in zip(straight[0], resumed[0]):
+        gh.assert_bits(a, b, "weights after resume")
+    for a, b in zip(straight[1], resumed[1]):
+        gh.assert_bits(a, b, "momentum after resume")
+    gh.assert_bits(straight[2], resumed[2], "reduced gradient of the last step")
