@@ -68,6 +68,8 @@ def parse():
                     help="16-byte vectors per thread per tile (0 = the library picks from the size)")
     ap.add_argument("--state-store-sc1", type=int, default=-1, choices=[-1, 0, 1],
                     help="store policy of weights / momentum (-1 = the library's default)")
+    ap.add_argument("--alternate-sweep", type=int, default=-1, choices=[-1, 0, 1],
+                    help="alternate the sweep direction between steps (-1 = the library's default)")
     ap.add_argument("--kernel-only", action="store_true",
                     help="time only mc_reduce_update launches (for profiler runs)")
     return ap.parse_args()
@@ -297,6 +299,8 @@ def main():
     torch.cuda.set_device(0)
     if args.unroll:
         mc.set_option(mc.OPT_RU_UNROLL, args.unroll)
+    if args.alternate_sweep >= 0:
+        mc.set_option(mc.OPT_ALTERNATE_SWEEP, args.alternate_sweep)
     if args.state_store_sc1 >= 0:
         mc.set_option(mc.OPT_STATE_STORE_SC1, args.state_store_sc1)
     cfg = wl.workload(args.workload)

@@ -289,8 +289,12 @@ enum {
     MC_OPT_PACK_NONTEMPORAL = 3,   /* pack/unpack: bit 0 streaming access to the per-layer
                                       tensors, bit 1 streaming access to the flat payload
                                       (non-temporal loads, write-through stores) */
-    MC_OPT_STATE_STORE_SC1 = 4     /* 0 / 1: full tiles store updated weights and momentum with the
+    MC_OPT_STATE_STORE_SC1 = 4,    /* 0 / 1: full tiles store updated weights and momentum with the
                                       agent-scope (write-through) bit */
+    MC_OPT_ALTERNATE_SWEEP = 5     /* 0 / 1: when weights + momentum exceed the 256 MB memory-side
+                                      cache, successive whole-payload update calls on a layout walk
+                                      the payload in opposite directions, so that the state written
+                                      last is read first */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

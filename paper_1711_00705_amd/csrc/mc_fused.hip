@@ -34,6 +34,7 @@ struct FusedArgs {
     int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
     int32_t n_segs;
+    int32_t reverse;                // walk the launch's tiles from the last to the first
     float* const* w;                    // pointer tables of weights and momentum (per layer)
     float* const* v;
     float* g;                           // flat payload, may be null
@@ -201,11 +202,12 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
     const int np = P > 0 ? P : Prt;
     const mc::Hyper hp = mc::resolve(a.up);
 
+    const int blk = a.reverse ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x);
     int s = 0;
-    while (s + 1 < a.n_segs && int(blockIdx.x) >= a.first_block[s + 1]) ++s;
+    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
     const int64_t lo = a.lo[s];
     const int64_t hi = a.hi[s];
-    const int64_t base = lo + int64_t(int(blockIdx.x) - a.first_block[s]) * kTile;  // multiple of 256
+    const int64_t base = lo + int64_t(blk - a.first_block[s]) * kTile;  // multiple of 256
     const int64_t end = base + kTile < hi ? base + kTile : hi;
     const float* const* const* xs = a.x + s * np;
 
@@ -473,6 +475,7 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     FusedArgs a;
+    a.reverse = (!n_terms && mc::sweep_reversed(L)) ? 1 : 0;   // role calls come several to a step
     a.w = weights ? reinterpret_cast<float* const*>(weights->d_ptrs) : nullptr;
     a.v = momentum ? reinterpret_cast<float* const*>(momentum->d_ptrs) : nullptr;
     a.g = static_cast<float*>(grad_out);

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <cstdint>
 #include <mutex>
 #include <utility>
@@ -41,6 +42,9 @@ struct mc_layout {
     std::vector<int64_t> off;         // n+1
     std::vector<int64_t> bounds;      // k+1
     std::vector<int32_t> tile_first;  // ceil(N / kLookupElems) + 1
+    // Parity of the next whole-payload update call: successive steps sweep the payload in opposite
+    // directions (see sweep_reversed()).
+    mutable std::atomic<uint32_t> sweep{0};
     std::mutex mu;                    // guards dev[] during prepare / destroy
     mc::DeviceTables dev[mc::kMaxDevices];
 };
@@ -72,6 +76,14 @@ inline bool overlaps(const void* a, uint64_t na, const void* b, uint64_t nb) {
 int device_tables(mc_layout* L, const DeviceTables** out);
 
 int option(int which);
+// Should this whole-payload update call walk the payload backwards?  Weights and momentum are the
+// only data that come back every step.  When they exceed the 256 MB memory-side cache, sweeping
+// the payload in the same direction every step evicts each line long before it is needed again;
+// alternating the direction makes the most recently written part the first to be read.  Measured on
+// a bare loop: 480 MB of state 5.8 -> 6.7 TB/s, 1.1 GB (VGG-16) 5.4 -> 5.8 TB/s; no gain when the
+// state fits, so smaller payloads keep one direction.  The result does not depend on the direction
+// (the step is elementwise).
+bool sweep_reversed(const mc_layout* L);
 // Vectors per thread per tile for a launch over `elems` elements (honours MC_OPT_RU_UNROLL).
 int unroll_for(int64_t elems);
 

@@ -13,6 +13,7 @@ std::atomic<int> g_ru_unroll{0};
 std::atomic<int> g_ru_nontemporal{1};
 std::atomic<int> g_pack_nontemporal{3};
 std::atomic<int> g_state_store_sc1{1};
+std::atomic<int> g_alternate_sweep{1};
 
 }  // namespace
 
@@ -32,12 +33,22 @@ int unroll_for(int64_t elems) {
     return elems / 2048 >= 8192 ? 2 : 1;
 }
 
+bool sweep_reversed(const mc_layout* L) {
+    if (!g_alternate_sweep.load(std::memory_order_relaxed)) return false;
+    // Only when weights + momentum (8 bytes per element) cannot stay in the 256 MB memory-side
+    // cache anyway; while they fit, a fixed direction measured 1-2 % faster.
+    constexpr int64_t kMemorySideCacheBytes = int64_t(256) << 20;
+    if (L->N * 8 <= kMemorySideCacheBytes) return false;
+    return (L->sweep.fetch_add(1, std::memory_order_relaxed) & 1u) != 0;
+}
+
 int option(int which) {
     switch (which) {
         case MC_OPT_RU_UNROLL: return g_ru_unroll.load(std::memory_order_relaxed);
         case MC_OPT_RU_NONTEMPORAL: return g_ru_nontemporal.load(std::memory_order_relaxed);
         case MC_OPT_PACK_NONTEMPORAL: return g_pack_nontemporal.load(std::memory_order_relaxed);
         case MC_OPT_STATE_STORE_SC1: return g_state_store_sc1.load(std::memory_order_relaxed);
+        case MC_OPT_ALTERNATE_SWEEP: return g_alternate_sweep.load(std::memory_order_relaxed);
         default: return -1;
     }
 }
@@ -151,6 +162,10 @@ int mc_set_option(int option, int value) {
         case MC_OPT_STATE_STORE_SC1:
             if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
             g_state_store_sc1.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_ALTERNATE_SWEEP:
+            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
+            g_alternate_sweep.store(value, std::memory_order_relaxed);
             return MC_OK;
         default:
             return MC_ERR_INVALID_ARG;

@@ -33,6 +33,7 @@ struct RuArgs {
     int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
     int32_t n_segs;
+    int32_t reverse;                // walk the launch's tiles from the last to the first
     float* g;                       // may be null when UPDATE
     float* w;                       // unused when !UPDATE
     float* v;
@@ -73,11 +74,12 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
     const mc::Hyper hp = mc::resolve(a.up);
 
     // blockIdx -> (segment, tile); a handful of scalar compares.
+    const int blk = a.reverse ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x);
     int s = 0;
-    while (s + 1 < a.n_segs && int(blockIdx.x) >= a.first_block[s + 1]) ++s;
+    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
     const int64_t lo = a.lo[s];
     const int64_t hi = a.hi[s];
-    const int64_t base = lo + int64_t(int(blockIdx.x) - a.first_block[s]) * kTile;
+    const int64_t base = lo + int64_t(blk - a.first_block[s]) * kTile;
     const float* const* xs = a.x + s * np;
 
     if (base + kTile <= hi) {
@@ -285,6 +287,8 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     RuArgs a;
+    // Only the plain whole-payload step alternates: packets and role calls come several to a step.
+    a.reverse = (!n_terms && r_lo == 0 && r_hi == L->N && mc::sweep_reversed(L)) ? 1 : 0;
     a.g = static_cast<float*>(grad_out);
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);

@@ -157,7 +157,8 @@ def test_options():
     for opt, good, bad in ((mc.OPT_RU_UNROLL, (0, 1, 2), (-1, 3, 4)),
                            (mc.OPT_RU_NONTEMPORAL, (0, 1), (-1, 2)),
                            (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4)),
-                           (mc.OPT_STATE_STORE_SC1, (0, 1), (-1, 2))):
+                           (mc.OPT_STATE_STORE_SC1, (0, 1), (-1, 2)),
+                           (mc.OPT_ALTERNATE_SWEEP, (0, 1), (-1, 2))):
         keep = mc.get_option(opt)
         for g in good:
             mc.set_option(opt, g)

@@ -367,3 +367,26 @@ def test_pack_and_unpack_through_tensor_sets_with_thousands_of_tensors():
         assert e.value.code == mc.ERR_OVERLAP
         for s_ in (tset, oset, alias):
             s_.destroy()
+
+
+@pytest.mark.parametrize("alternate", [0, 1])
+def test_sweep_direction_does_not_change_bits(alternate):
+    """Successive whole-payload calls on one layout walk the payload in opposite directions
+    (a cache-reuse measure); the same step repeated from the same state must give the same bits
+    whichever direction it happens to get, in both forms of the step."""
+    keep = mc.get_option(mc.OPT_ALTERNATE_SWEEP)
+    mc.set_option(mc.OPT_ALTERNATE_SWEEP, alternate)
+    try:
+        # above 32 Mi elements (256 MB of weights + momentum) the calls alternate when enabled
+        sizes = [30000, 12, 4099, 70001] if alternate == 0 else [20_000_000, 12, 4099, 14_000_001]
+        st = gh.Step(sizes, 3)
+        fs = gh.FusedStep(sizes, 3)
+        xs, w, v = _inputs(sizes, 2, v_zero=False)
+        order = wl.rotation_order(3, 2)
+        for rep in range(3 if alternate == 0 else 2):      # the layouts persist across repetitions
+            gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=order)
+            st.check(gpu, ref, 0.1, 0.9, 1e-4, f"staged rep {rep}")
+            gpu, ref = fs.run(xs, w, v, 0.1, 0.9, 1e-4, order=order, misalign=[0])
+            fs.check(gpu, ref, f"fused rep {rep}")
+    finally:
+        mc.set_option(mc.OPT_ALTERNATE_SWEEP, keep)
