@@ -153,7 +153,29 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
                 acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
             }
         }
-        for (int q = 1; q < np; ++q) {
+        // Four terms' loads are issued before their adds (more bytes in flight); the adds still
+        // run strictly left to right.
+        int q = 1;
+        for (; q + 4 <= np; q += 4) {
+            float4 t[4][U];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float* xq = xs[q + r][t0] + rel;
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (on[u]) t[r][u] = load4<NT>(xq + j[u]);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    acc[u].x = acc[u].x + t[r][u].x;
+                    acc[u].y = acc[u].y + t[r][u].y;
+                    acc[u].z = acc[u].z + t[r][u].z;
+                    acc[u].w = acc[u].w + t[r][u].w;
+                }
+        }
+        for (; q < np; ++q) {
             const float* xq = xs[q][t0] + rel;
 #pragma unroll
             for (int u = 0; u < U; ++u) {

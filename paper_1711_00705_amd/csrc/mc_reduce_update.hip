@@ -121,7 +121,26 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
                 }
                 acc[u] = load4<NT_IN>(xs[0] + idx[u]);
             }
-            for (int q = 1; q < np; ++q) {
+            // Four terms' loads are issued before their adds (more bytes in flight); the adds
+            // still run strictly left to right.
+            int q = 1;
+            for (; q + 4 <= np; q += 4) {
+                float4 t[4][U];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) t[r][u] = load4<NT_IN>(xs[q + r] + idx[u]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        acc[u].x = acc[u].x + t[r][u].x;
+                        acc[u].y = acc[u].y + t[r][u].y;
+                        acc[u].z = acc[u].z + t[r][u].z;
+                        acc[u].w = acc[u].w + t[r][u].w;
+                    }
+            }
+            for (; q < np; ++q) {
                 const float* xq = xs[q];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
