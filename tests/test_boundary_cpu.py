@@ -250,5 +250,6 @@ def test_reduce_update_range_rejects_before_launch():
     assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 256, 256) == mc.OK                  # empty packet
     assert _code(rr, L, x, None, g, w + 4, v, .1, .9, 0., 0, 256) == mc.ERR_ALIGN
     assert _code(rr, L, x, None, g, w, v, .1, .9, 0., 0, 256, 0, [2, 3], [1, 1]) == mc.ERR_INVALID_ARG  # n_terms > P
-    L2 = mc.Layout([1000], 1)             # N = 1000: a range may end at N
-    assert _code(rr, L2, x, None, g, w, v, .1, .9, 0., 768, 1000, 0) in (mc.OK, mc.ERR_HIP)
+    L2 = mc.Layout([1000], 1)             # N = 1000: a range may end at N (and then must be aligned)
+    assert _code(rr, L2, x, None, g, w + 4, v, .1, .9, 0., 768, 1000, 0) == mc.ERR_ALIGN
+    assert _code(rr, L2, x, None, g, w, v, .1, .9, 0., 768, 999, 0) == mc.ERR_INVALID_ARG
