@@ -127,21 +127,29 @@ def _check(code: int, where: str) -> None:
         raise McError(code, where)
 
 
-def ptr_table(ptrs: Sequence[Optional[int]]):
-    """A host array of device addresses, reusable across calls (saves rebuilding it)."""
-    tab = (ctypes.c_void_p * max(len(ptrs), 1))()
-    for i, p in enumerate(ptrs):
-        tab[i] = p
-    tab.count = len(ptrs)
-    return tab
+class PtrTable:
+    """A host array of device addresses (or handles) that can be passed to the library as is
+    and reused across calls (saves rebuilding it on every step)."""
+
+    def __init__(self, ptrs: Sequence[Optional[int]], keep=None):
+        self.count = len(ptrs)
+        self._array = (ctypes.c_void_p * max(self.count, 1))()
+        for i, p in enumerate(ptrs):
+            self._array[i] = p
+        self._as_parameter_ = ctypes.cast(self._array, ctypes.POINTER(ctypes.c_void_p))  # what ctypes passes
+        self.keep = keep                       # objects whose lifetime the table depends on
 
 
-def _ptr_table(ptrs):
-    return ptrs if isinstance(ptrs, ctypes.Array) else ptr_table(ptrs)
+def ptr_table(ptrs: Sequence[Optional[int]]) -> PtrTable:
+    return PtrTable(ptrs)
+
+
+def _ptr_table(ptrs) -> PtrTable:
+    return ptrs if isinstance(ptrs, PtrTable) else PtrTable(ptrs)
 
 
 def _count(ptrs) -> int:
-    return ptrs.count if isinstance(ptrs, ctypes.Array) else len(ptrs)
+    return ptrs.count if isinstance(ptrs, PtrTable) else len(ptrs)
 
 
 class Layout:
@@ -323,19 +331,14 @@ def unpack_set(layout: Layout, flat_ptr: Optional[int], tensors: TensorSet, stre
                              stream or None), "mc_unpack_set")
 
 
-def set_table(sets):
-    """A host array of tensor-set handles, reusable across calls."""
-    tab = (ctypes.c_void_p * max(len(sets), 1))()
-    for i, s in enumerate(sets):
-        tab[i] = s.handle if s is not None else None
-    tab.count = len(sets)
-    tab.keep = list(sets)
-    return tab
+def set_table(sets) -> PtrTable:
+    """A host array of tensor-set handles, reusable across calls (keeps the sets alive)."""
+    return PtrTable([s.handle.value if s is not None else None for s in sets], keep=list(sets))
 
 
 def fused_step(layout: Layout, contrib_sets, order, grad_out_ptr: Optional[int], weights: TensorSet,
                momentum: TensorSet, lr: float, mu: float, wd: float, stream: int = 0) -> None:
-    tab = contrib_sets if isinstance(contrib_sets, ctypes.Array) else set_table(contrib_sets)
+    tab = contrib_sets if isinstance(contrib_sets, PtrTable) else set_table(contrib_sets)
     P = tab.count
     optr = None
     if order is not None:
@@ -390,7 +393,7 @@ def reduce_update_ex(layout: Layout, contrib_ptrs, order, grad_out_ptr, weights_
 def fused_step_ex(layout: Layout, contrib_sets, order, grad_out_ptr, weights: "TensorSet",
                   momentum: "TensorSet", spec: UpdateSpec, stream: int = 0, n_terms=None,
                   do_update=None) -> None:
-    tab = contrib_sets if isinstance(contrib_sets, ctypes.Array) else set_table(contrib_sets)
+    tab = contrib_sets if isinstance(contrib_sets, PtrTable) else set_table(contrib_sets)
     _o, optr = _order_ptr(order, layout.k, tab.count)
     ntp = dup = None
     if n_terms is not None or do_update is not None:
