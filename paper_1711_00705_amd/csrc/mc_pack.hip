@@ -71,6 +71,36 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
     const int64_t tile_base = tile * kTileElems;
     const int32_t t_tile = max(tile_first[tile_base / mc::kLookupElems], t0);
 
+    // Whole tile inside one tensor (and inside this launch's range) with a 16-byte aligned
+    // tensor side: nearly all bytes of a CNN payload.  Everything deciding it is uniform over
+    // the workgroup, so the lookups are scalar loads, and all V loads precede the first store.
+    if (tile_base >= lo && tile_base + kTileElems <= hi) {
+        const int64_t t_lo = off[t_tile];
+        const int64_t t_hi = off[t_tile + 1];
+        if (t_lo <= tile_base && tile_base + kTileElems <= t_hi) {
+            uint32_t* tens =
+                static_cast<uint32_t*>(table ? table[t_tile] : ptrs.p[t_tile - t0]) + (tile_base - t_lo);
+            if ((reinterpret_cast<uintptr_t>(tens) & 15) == 0) {
+                uint32_t* fl = flat + tile_base;
+                uint4 q[V];
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    const int e = (j * kThreads + int(threadIdx.x)) * 4;
+                    q[j] = UNPACK ? ld4<NT_F>(fl + e) : ld4<NT_T>(tens + e);
+                }
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    const int e = (j * kThreads + int(threadIdx.x)) * 4;
+                    if (UNPACK)
+                        st4<NT_T>(tens + e, q[j]);
+                    else
+                        st4<NT_F>(fl + e, q[j]);
+                }
+                return;
+            }
+        }
+    }
+
 #pragma unroll
     for (int j = 0; j < V; ++j) {
         const int64_t i = tile_base + (int64_t(j) * kThreads + threadIdx.x) * 4;
