@@ -70,6 +70,8 @@ def parse():
                     help="store policy of weights / momentum (-1 = the library's default)")
     ap.add_argument("--alternate-sweep", type=int, default=-1, choices=[-1, 0, 1],
                     help="alternate the sweep direction between steps (-1 = the library's default)")
+    ap.add_argument("--xcd-run", type=int, default=-1,
+                    help="consecutive tiles per die, 0..64 (-1 = the library's default)")
     ap.add_argument("--kernel-only", action="store_true",
                     help="time only mc_reduce_update launches (for profiler runs)")
     return ap.parse_args()
@@ -303,6 +305,8 @@ def main():
         mc.set_option(mc.OPT_ALTERNATE_SWEEP, args.alternate_sweep)
     if args.state_store_sc1 >= 0:
         mc.set_option(mc.OPT_STATE_STORE_SC1, args.state_store_sc1)
+    if args.xcd_run >= 0:
+        mc.set_option(mc.OPT_XCD_RUN, args.xcd_run)
     cfg = wl.workload(args.workload)
     N, P, k = cfg.total, cfg.P, cfg.k
     order = None if args.order == "identity" else wl.rotation_order(k, P)

@@ -291,10 +291,14 @@ enum {
                                       (non-temporal loads, write-through stores) */
     MC_OPT_STATE_STORE_SC1 = 4,    /* 0 / 1: full tiles store updated weights and momentum with the
                                       agent-scope (write-through) bit */
-    MC_OPT_ALTERNATE_SWEEP = 5     /* 0 / 1: when weights + momentum exceed the 256 MB memory-side
+    MC_OPT_ALTERNATE_SWEEP = 5,    /* 0 / 1: when weights + momentum exceed the 256 MB memory-side
                                       cache, successive whole-payload update calls on a layout walk
                                       the payload in opposite directions, so that the state written
                                       last is read first */
+    MC_OPT_XCD_RUN = 6             /* 0..64: workgroups are dealt to the chip's 8 dies round-robin;
+                                      with a value r > 1 every kernel permutes its tiles so that each
+                                      die walks r consecutive tiles (neighbouring tiles then share one
+                                      L2).  0 or 1: tile = workgroup index. */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

@@ -18,6 +18,7 @@
 #include <vector>
 
 #include "mc_internal.h"
+#include "mc_tiles.h"
 #include "mc_update.h"
 
 #pragma clang fp contract(off)
@@ -35,6 +36,7 @@ struct FusedArgs {
     int32_t first_block[kMaxSegs + 1];
     int32_t n_segs;
     int32_t reverse;                // walk the launch's tiles from the last to the first
+    int32_t xcd_run;                // consecutive tiles per die (see mc_tiles.h); <= 1: plain
     float* const* w;                    // pointer tables of weights and momentum (per layer)
     float* const* v;
     float* g;                           // flat payload, may be null
@@ -224,7 +226,8 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
     const int np = P > 0 ? P : Prt;
     const mc::Hyper hp = mc::resolve(a.up);
 
-    const int blk = a.reverse ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x);
+    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
+    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
     int s = 0;
     while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
     const int64_t lo = a.lo[s];
@@ -498,6 +501,7 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
 
     FusedArgs a;
     a.reverse = (!n_terms && mc::sweep_reversed(L)) ? 1 : 0;   // role calls come several to a step
+    a.xcd_run = mc::option(MC_OPT_XCD_RUN);
     a.w = weights ? reinterpret_cast<float* const*>(weights->d_ptrs) : nullptr;
     a.v = momentum ? reinterpret_cast<float* const*>(momentum->d_ptrs) : nullptr;
     a.g = static_cast<float*>(grad_out);

@@ -14,6 +14,7 @@ std::atomic<int> g_ru_nontemporal{1};
 std::atomic<int> g_pack_nontemporal{3};
 std::atomic<int> g_state_store_sc1{1};
 std::atomic<int> g_alternate_sweep{1};
+std::atomic<int> g_xcd_run{0};
 
 }  // namespace
 
@@ -49,6 +50,7 @@ int option(int which) {
         case MC_OPT_PACK_NONTEMPORAL: return g_pack_nontemporal.load(std::memory_order_relaxed);
         case MC_OPT_STATE_STORE_SC1: return g_state_store_sc1.load(std::memory_order_relaxed);
         case MC_OPT_ALTERNATE_SWEEP: return g_alternate_sweep.load(std::memory_order_relaxed);
+        case MC_OPT_XCD_RUN: return g_xcd_run.load(std::memory_order_relaxed);
         default: return -1;
     }
 }
@@ -166,6 +168,10 @@ int mc_set_option(int option, int value) {
         case MC_OPT_ALTERNATE_SWEEP:
             if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
             g_alternate_sweep.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_XCD_RUN:
+            if (value < 0 || value > 64) return MC_ERR_INVALID_ARG;
+            g_xcd_run.store(value, std::memory_order_relaxed);
             return MC_OK;
         default:
             return MC_ERR_INVALID_ARG;

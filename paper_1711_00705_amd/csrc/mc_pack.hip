@@ -15,6 +15,7 @@
 #include <algorithm>
 
 #include "mc_internal.h"
+#include "mc_tiles.h"
 
 namespace {
 
@@ -62,10 +63,11 @@ __device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
 template <bool UNPACK, bool NT_T, bool NT_F, int V>
 __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
     PtrBatch ptrs, void* const* __restrict__ table, const int64_t* __restrict__ off,
-    const int32_t* __restrict__ tile_first, uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0) {
+    const int32_t* __restrict__ tile_first, uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0,
+    int xcd_run) {
     constexpr int64_t kTileElems = int64_t(kThreads) * 4 * V;
     static_assert(kTileElems % mc::kLookupElems == 0, "tiles start on lookup entries");
-    const int64_t tile = tile0 + blockIdx.x;
+    const int64_t tile = tile0 + mc::xcd_tile(int(blockIdx.x), int(gridDim.x), xcd_run);
     const int64_t lo = off[t0];
     const int64_t hi = off[t1];
     const int64_t tile_base = tile * kTileElems;
@@ -164,14 +166,15 @@ int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch&
     if (tile_end - tile0 > 0x7fffffff) return MC_ERR_INVALID_ARG;
     const dim3 grid(unsigned(tile_end - tile0)), block(kThreads);
     uint32_t* f = static_cast<uint32_t*>(flat);
+    const int xcd_run = mc::option(MC_OPT_XCD_RUN);
 #define MC_GS_LAUNCH(NT_T, NT_F)                                                                       \
     do {                                                                                               \
         if (vec == 2)                                                                                  \
             hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, 0, s, batch, \
-                               table, dt->off, dt->tile_first, f, t0, t1, tile0);                      \
+                               table, dt->off, dt->tile_first, f, t0, t1, tile0, xcd_run);             \
         else                                                                                           \
             hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, 0, s, batch, \
-                               table, dt->off, dt->tile_first, f, t0, t1, tile0);                      \
+                               table, dt->off, dt->tile_first, f, t0, t1, tile0, xcd_run);             \
     } while (0)
     switch (nt & 3) {
         case 0: MC_GS_LAUNCH(false, false); break;

@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "mc_internal.h"
+#include "mc_tiles.h"
 #include "mc_update.h"
 
 #pragma clang fp contract(off)
@@ -34,6 +35,7 @@ struct RuArgs {
     int32_t first_block[kMaxSegs + 1];
     int32_t n_segs;
     int32_t reverse;                // walk the launch's tiles from the last to the first
+    int32_t xcd_run;                // consecutive tiles per die (see mc_tiles.h); <= 1: plain
     float* g;                       // may be null when UPDATE
     float* w;                       // unused when !UPDATE
     float* v;
@@ -74,7 +76,8 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
     const mc::Hyper hp = mc::resolve(a.up);
 
     // blockIdx -> (segment, tile); a handful of scalar compares.
-    const int blk = a.reverse ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x);
+    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
+    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
     int s = 0;
     while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
     const int64_t lo = a.lo[s];
@@ -308,6 +311,7 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     RuArgs a;
     // Only the plain whole-payload step alternates: packets and role calls come several to a step.
     a.reverse = (!n_terms && r_lo == 0 && r_hi == L->N && mc::sweep_reversed(L)) ? 1 : 0;
+    a.xcd_run = mc::option(MC_OPT_XCD_RUN);
     a.g = static_cast<float*>(grad_out);
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);

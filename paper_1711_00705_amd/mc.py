@@ -27,6 +27,7 @@ OPT_RU_NONTEMPORAL = 2
 OPT_PACK_NONTEMPORAL = 3
 OPT_STATE_STORE_SC1 = 4
 OPT_ALTERNATE_SWEEP = 5
+OPT_XCD_RUN = 6
 ROLE_LEAF, ROLE_INNER, ROLE_ROOT = 0, 1, 2
 
 _i64p = ctypes.POINTER(ctypes.c_int64)

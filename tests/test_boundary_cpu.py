@@ -158,7 +158,8 @@ def test_options():
                            (mc.OPT_RU_NONTEMPORAL, (0, 1), (-1, 2)),
                            (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4)),
                            (mc.OPT_STATE_STORE_SC1, (0, 1), (-1, 2)),
-                           (mc.OPT_ALTERNATE_SWEEP, (0, 1), (-1, 2))):
+                           (mc.OPT_ALTERNATE_SWEEP, (0, 1), (-1, 2)),
+                           (mc.OPT_XCD_RUN, (0, 1, 8, 64), (-1, 65))):
         keep = mc.get_option(opt)
         for g in good:
             mc.set_option(opt, g)

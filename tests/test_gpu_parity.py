@@ -390,3 +390,24 @@ def test_sweep_direction_does_not_change_bits(alternate):
             fs.check(gpu, ref, f"fused rep {rep}")
     finally:
         mc.set_option(mc.OPT_ALTERNATE_SWEEP, keep)
+
+
+@pytest.mark.parametrize("run", [2, 5, 16, 64])
+def test_tile_order_does_not_change_bits(run):
+    """With MC_OPT_XCD_RUN every kernel permutes its tiles so that each die walks `run`
+    neighbouring tiles; tiles are independent, so pack, sum, update and unpack must give the
+    plain order's bits.  Sizes: several permuted spans plus a ragged rest, several colours."""
+    keep = mc.get_option(mc.OPT_XCD_RUN)
+    mc.set_option(mc.OPT_XCD_RUN, run)
+    try:
+        sizes = [300_000, 12, 4099, 700_001, 0, 1_000_000, 37]
+        xs, w, v = _inputs(sizes, 3, v_zero=False)
+        order = wl.rotation_order(5, 3)
+        st = gh.Step(sizes, 5)
+        gpu, ref = st.run(xs, w, v, 0.1, 0.9, 1e-4, order=order)
+        st.check(gpu, ref, 0.1, 0.9, 1e-4, f"staged xcd_run {run}")
+        fs = gh.FusedStep(sizes, 5)
+        gpu, ref = fs.run(xs, w, v, 0.1, 0.9, 1e-4, order=order, misalign=[0])
+        fs.check(gpu, ref, f"fused xcd_run {run}")
+    finally:
+        mc.set_option(mc.OPT_XCD_RUN, keep)
