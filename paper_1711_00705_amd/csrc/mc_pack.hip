@@ -29,15 +29,21 @@ struct PtrBatch {
 };
 
 typedef uint32_t native_u4 __attribute__((ext_vector_type(4)));
+// Every buffer is device global memory.  Tensor pointers arrive through memory (the pointer batch
+// or a tensor set's table) as generic pointers; dereferencing through global-address-space types
+// lets the compiler emit global_ instead of flat_ instructions.
+typedef __attribute__((address_space(1))) native_u4 global_u4;
+typedef __attribute__((address_space(1))) uint32_t global_u1;
 
 template <bool NT>
 __device__ __forceinline__ uint4 ld4(const uint32_t* p) {
-    if (NT) {
-        const native_u4 r = __builtin_nontemporal_load(reinterpret_cast<const native_u4*>(p));
-        return make_uint4(r.x, r.y, r.z, r.w);
-    }
-    return *reinterpret_cast<const uint4*>(p);
+    const global_u4* gp = (const global_u4*)p;
+    const native_u4 r = NT ? __builtin_nontemporal_load(gp) : *gp;
+    return make_uint4(r.x, r.y, r.z, r.w);
 }
+
+__device__ __forceinline__ uint32_t ld1(const uint32_t* p) { return *(const global_u1*)p; }
+__device__ __forceinline__ void st1(uint32_t* p, uint32_t x) { *(global_u1*)p = x; }
 
 // Streaming store: the agent-scope (write-through) bit measured faster than the non-temporal
 // hint for copy-shaped kernels on this part (+15 % at 28 MB, +2 % at 100 MB, equal at 550 MB).
@@ -51,7 +57,8 @@ __device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
         const native_u4 val = {q.x, q.y, q.z, q.w};
         asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(val) : "memory");
     } else {
-        *reinterpret_cast<uint4*>(p) = q;
+        const native_u4 val = {q.x, q.y, q.z, q.w};
+        *(global_u4*)p = val;
     }
 }
 
@@ -121,16 +128,16 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
                     st4<NT_F>(flat + i, ld4<NT_T>(src));
             } else if (UNPACK) {
                 const uint4 q = ld4<NT_F>(flat + i);
-                src[0] = q.x;
-                src[1] = q.y;
-                src[2] = q.z;
-                src[3] = q.w;
+                st1(src + 0, q.x);
+                st1(src + 1, q.y);
+                st1(src + 2, q.z);
+                st1(src + 3, q.w);
             } else {
                 uint4 q;
-                q.x = src[0];
-                q.y = src[1];
-                q.z = src[2];
-                q.w = src[3];
+                q.x = ld1(src + 0);
+                q.y = ld1(src + 1);
+                q.z = ld1(src + 2);
+                q.w = ld1(src + 3);
                 st4<NT_F>(flat + i, q);
             }
             continue;
@@ -143,9 +150,9 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
             while (off[t + 1] <= idx) ++t;
             uint32_t* elem = static_cast<uint32_t*>(table ? table[t] : ptrs.p[t - t0]) + (idx - off[t]);
             if (UNPACK)
-                *elem = flat[idx];
+                st1(elem, ld1(flat + idx));
             else
-                flat[idx] = *elem;
+                st1(flat + idx, ld1(elem));
         }
     }
 }
