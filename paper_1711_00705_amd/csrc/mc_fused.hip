@@ -223,6 +223,7 @@ template <int P, int U, bool HAS_G, bool UPDATE, bool NT>
 __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int Prt) {
     static_assert(HAS_G || UPDATE, "a launch must produce something");
     constexpr int kTile = kThreads * 4 * U;
+    static_assert(kTile % mc::kLookupElems == 0, "tiles start on lookup entries");
     const int np = P > 0 ? P : Prt;
     const mc::Hyper hp = mc::resolve(a.up);
 
@@ -236,9 +237,10 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
     const int64_t end = base + kTile < hi ? base + kTile : hi;
     const float* const* const* xs = a.x + s * np;
 
-    // The tensor holding the tile's first element (block-uniform).
-    int32_t t0 = a.first_tensor[base / mc::kLookupElems];
-    while (a.off[t0 + 1] <= base) ++t0;
+    // The tensor holding the tile's first element (block-uniform).  `base` is a multiple of the
+    // lookup granularity, so the table entry is that tensor itself: no scan of off[] is needed and
+    // the loads of its bounds and of the operands' base pointers do not wait for one another.
+    const int32_t t0 = a.first_tensor[base / mc::kLookupElems];
     const int64_t t0_begin = a.off[t0];
     const int64_t t0_end = a.off[t0 + 1];
 
