@@ -16,7 +16,7 @@ namespace mc {
 
 constexpr int kXcds = 8;
 
-__device__ __forceinline__ int xcd_tile(int b, int n_blocks, int run) {
+__host__ __device__ __forceinline__ int xcd_tile(int b, int n_blocks, int run) {
     if (run <= 1) return b;
     const int span = kXcds * run;
     if (b >= n_blocks - n_blocks % span) return b;

@@ -5,6 +5,7 @@
 #include <vector>
 
 #include "mc.h"
+#include "mc_tiles.h"
 
 #define REQUIRE(c)                                                    \
     do {                                                              \
@@ -64,6 +65,20 @@ int main() {
                 REQUIRE(roots == 1);
             }
             for (int32_t r = 0; r < n; ++r) REQUIRE(mc_rank_roles(n, k, r, role.data(), cnt.data(), ch.data()) == MC_OK);
+        }
+    }
+    // The die-aware tile order is a permutation of the launch's tiles for every grid and run length,
+    // and inside a full span die x (workgroups x, x+8, ...) walks consecutive tiles.
+    for (int n : {0, 1, 7, 8, 63, 64, 65, 1000, 6834, 12479}) {
+        for (int run : {0, 1, 2, 3, 8, 16, 64}) {
+            std::vector<char> seen(size_t(n), 0);
+            for (int b = 0; b < n; ++b) {
+                const int t = mc::xcd_tile(b, n, run);
+                REQUIRE(t >= 0 && t < n && !seen[t]);
+                seen[t] = 1;
+                if (run > 1 && b + mc::kXcds < n - n % (mc::kXcds * run) && (b % (mc::kXcds * run)) / mc::kXcds < run - 1)
+                    REQUIRE(mc::xcd_tile(b + mc::kXcds, n, run) == t + 1);
+            }
         }
     }
     float lr = 0.f;
