@@ -368,7 +368,11 @@ def main():
         mc.unpack(L, w.data_ptr(), w_table, sh)
 
     def fused_step(i, ev=None):
+        if ev:
+            ev[0].record(stream)
         mc.fused_step(L, tsets[i % n_sets], order, g.data_ptr(), fw_set, fv_set, cfg.lr, cfg.mu, cfg.wd, sh)
+        if ev:
+            ev[1].record(stream)
 
     fused = args.path == "fused"
     step = fused_step if fused else staged_step
@@ -461,6 +465,11 @@ def main():
     other_ms, other_k_ms = timed_steps(staged_step if fused else fused_step, args.warmup, args.steps,
                                        per_step_events=fused)
 
+    # Median and minimum of single launches of the fused kernel, from one event pair per launch in a
+    # separate untimed pass (the event packets between launches add a few microseconds to each, which
+    # is why the timed region above brackets all its launches with one pair instead).
+    _, fused_each = timed_steps(fused_step, 2, max(10, min(args.steps, 100)), per_step_events=True)
+
     # ---- the pieces on their own (events around back-to-back launches), and the copy yardstick
     def timed(fn, reps):
         a = torch.cuda.Event(enable_timing=True)
@@ -517,7 +526,9 @@ def main():
                    "step_bytes": step_bytes},
         "pct_of_hbm_peak": round(100 * step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
         "fused_step": {"ms_per_step": round(fused_ms, 4), "kernel_ms": round(float(fused_k.mean()), 4),
-                       "GBps": round(kernel_bytes / float(fused_k.mean()) / 1e6, 1), "step_bytes": kernel_bytes},
+                       "GBps": round(kernel_bytes / float(fused_k.mean()) / 1e6, 1), "step_bytes": kernel_bytes,
+                       "single_launch_ms_median": round(float(np.median(fused_each)), 4),
+                       "single_launch_ms_min": round(float(fused_each.min()), 4)},
         "staged_step": {"ms_per_step": round(staged_ms, 4), "GBps": round(staged_bytes / staged_ms / 1e6, 1),
                         "step_bytes": staged_bytes,
                         "reduce_update_ms": round(float(staged_k.mean()), 4),
