@@ -28,6 +28,12 @@
  *     (NULL = the default stream) and return without synchronising.
  *   - A layout is immutable after mc_layout_prepare and may then be used from several host
  *     threads and streams at once.
+ *   - What validation cannot see: a device pointer carries no length.  Every flat buffer of a
+ *     call must hold the layout's N elements and tensor t of a tensor list numel[t] elements,
+ *     all resident on the current device.  Null pointers, misalignment and overlap are
+ *     rejected; a buffer that is shorter than stated is not detectable on the host, and the
+ *     kernels then read or write past its end (a device memory fault).  The same holds for a
+ *     pointer that is not a device address.
  */
 #ifndef MC_H_
 #define MC_H_
