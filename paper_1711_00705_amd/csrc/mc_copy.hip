@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "mc_internal.h"
+#include "mc_mem.h"
 
 namespace {
 
@@ -28,10 +29,9 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(uint4* __restrict__ dst,
     for (int j = 0; j < kVecPerThread; ++j) {
         const int64_t i = base + int64_t(j) * kThreads;
         if (i < n_vec) {
-            // (s_nop: wait states the hardware needs before the data registers may be rewritten)
             typedef uint32_t native4 __attribute__((ext_vector_type(4)));
             const native4 val = {r[j].x, r[j].y, r[j].z, r[j].w};
-            asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(dst + i), "v"(val) : "memory");
+            mc::store128_sc1(dst + i, val);
         }
     }
 }

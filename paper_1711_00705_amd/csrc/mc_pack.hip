@@ -15,6 +15,7 @@
 #include <algorithm>
 
 #include "mc_internal.h"
+#include "mc_mem.h"
 #include "mc_tiles.h"
 
 namespace {
@@ -46,20 +47,14 @@ __device__ __forceinline__ uint32_t ld1(const uint32_t* p) { return *(const glob
 __device__ __forceinline__ void st1(uint32_t* p, uint32_t x) { *(global_u1*)p = x; }
 
 // Streaming store: the agent-scope (write-through) bit measured faster than the non-temporal
-// hint for copy-shaped kernels on this part (+15 % at 28 MB, +2 % at 100 MB, equal at 550 MB).
-// A 128-bit store with that bit has no C++ spelling, hence the asm.  The s_nop after it is
-// required: a store of more than 64 bits still reads its data registers for two wait states
-// after issue, the compiler's hazard recogniser cannot see into the asm, and a VALU write to
-// one of those registers in the very next instruction corrupted the stored value.
+// hint for copy-shaped kernels on this part.
 template <bool STREAM>
 __device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
-    if (STREAM) {
-        const native_u4 val = {q.x, q.y, q.z, q.w};
-        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(val) : "memory");
-    } else {
-        const native_u4 val = {q.x, q.y, q.z, q.w};
+    const native_u4 val = {q.x, q.y, q.z, q.w};
+    if (STREAM)
+        mc::store128_sc1(p, val);
+    else
         *(global_u4*)p = val;
-    }
 }
 
 // One launch covers tensors [t0, t1), i.e. flat elements [off[t0], off[t1]), tile by tile.
@@ -243,6 +238,7 @@ int run_set(mc_layout* L, const mc_tensor_set* S, void* flat, void* stream) {
     for (int i = 0; i < mc::kPackMaxPtrs; ++i) none.p[i] = nullptr;
     return launch_range<UNPACK>(L, dt, none, S->d_ptrs, flat, 0, L->n, static_cast<hipStream_t>(stream));
 }
+
 
 }  // namespace
 

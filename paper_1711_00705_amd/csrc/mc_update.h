@@ -14,6 +14,8 @@
 
 #include <cstdint>
 
+#include "mc_mem.h"
+
 namespace mc {
 
 // As passed in kernel arguments: immediate values, or a device pointer to {lr, mu, wd} that the
@@ -63,18 +65,14 @@ __device__ __forceinline__ void sgd(float g, float& w, float& v, const Hyper& h)
     v = vn;
 }
 
-// 128-bit store of updated weights / momentum.  With `sc1` the store carries the agent-scope
-// bit: the line is written through instead of lingering dirty in L2, which measured 3 % faster
-// on the ResNet-50-sized step (the values are re-read only by the next step, long after).
-// There is no C++ spelling for a 128-bit store with that bit, hence the asm; the compiler still
-// orders it after the loads that produce its operands.  The s_nop is required: a store of more
-// than 64 bits reads its data registers for two wait states after issue, and the compiler's
-// hazard recogniser cannot see into the asm to keep a following VALU write away from them.
+// 128-bit store of updated weights / momentum: written through with the agent-scope bit when
+// `sc1` (3 % faster on the ResNet-50-sized step: the values are re-read only by the next step, long
+// after), a plain store otherwise.
 __device__ __forceinline__ void store_state(float* p, const float4& q, bool sc1) {
     typedef float native4 __attribute__((ext_vector_type(4)));
     const native4 val = {q.x, q.y, q.z, q.w};
     if (sc1) {
-        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(val) : "memory");
+        store128_sc1(p, val);
     } else {
         *(__attribute__((address_space(1))) native4*)p = val;  // device global memory
     }
