@@ -52,7 +52,8 @@ enum {
     MC_ERR_ALIGN = -2,         /* a flat buffer is not 16-byte aligned / a tensor not 4-byte aligned */
     MC_ERR_OVERLAP = -3,       /* two buffers of one call overlap */
     MC_ERR_ALLOC = -4,         /* host allocation failed */
-    MC_ERR_HIP = -5            /* a HIP runtime call failed; see mc_last_hip_error() */
+    MC_ERR_HIP = -5,           /* a HIP runtime call failed; see mc_last_hip_error() */
+    MC_ERR_LIMIT = -6          /* the input exceeds a fixed capacity of the entry point called */
 };
 
 #define MC_MAX_P 32                 /* most contributions one call can sum */
@@ -100,6 +101,22 @@ int mc_layout_colour_bounds(const mc_layout* L, int64_t* b);
  * non-empty tensor), MC_ERR_ALIGN, MC_ERR_OVERLAP (a tensor overlaps flat), MC_ERR_HIP. */
 int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream);
 int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream);
+
+/* mc_pack for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same copies, same validation and same errors as
+ * mc_pack, but the call needs no prepared layout and performs no hipMalloc, hipFree, host-device
+ * copy or synchronisation: the two small lookup tables that the gather kernel reads are rebuilt on
+ * `stream`, ahead of the gather, in a fixed array of about 4 MiB inside the library's device image
+ * (one copy per GPU, held until the process ends; its address is looked up on the first call on each
+ * device, so make one call before starting a capture).
+ * Limits: at most MC_NOALLOC_MAX_TENSORS tensors and MC_NOALLOC_MAX_ELEMS elements in total;
+ * beyond either the call returns MC_ERR_LIMIT and touches nothing.
+ * Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (different
+ * streams, or several host threads) race on it and must be serialised by the caller; calls queued
+ * on one stream are safe. */
+#define MC_NOALLOC_MAX_TENSORS 256
+#define MC_NOALLOC_MAX_ELEMS (1 << 28)
+int mc_pack_noalloc(const mc_layout* L, const void* const* tensors, void* flat, void* stream);
 
 /* ---- a3 + a4: per-colour reduction fused with the SGD update -------------------------
  * Section 3, Algorithm 1 (intra-node sum, inter-node sum, then SGD on each GPU) and

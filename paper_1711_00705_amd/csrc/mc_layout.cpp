@@ -141,6 +141,7 @@ const char* mc_strerror(int code) {
         case MC_ERR_OVERLAP: return "buffers overlap";
         case MC_ERR_ALLOC: return "host allocation failed";
         case MC_ERR_HIP: return "HIP runtime call failed";
+        case MC_ERR_LIMIT: return "input exceeds the fixed capacity of this entry point";
         default: return "unknown error code";
     }
 }

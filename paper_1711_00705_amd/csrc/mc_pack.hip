@@ -240,6 +240,106 @@ int run_set(mc_layout* L, const mc_tensor_set* S, void* flat, void* stream) {
 }
 
 
+// ---- mc_pack for callers that may not allocate ------------------------------------------------
+// The gather kernel reads two tables (flat offsets, first tensor per 256 flat elements) that the
+// other entry points keep in device memory allocated by mc_layout_prepare.  Here they live in a
+// fixed array in the library's own device image and are rebuilt on the stream before every call.
+constexpr int64_t kNoAllocMaxElems = int64_t(MC_NOALLOC_MAX_ELEMS);
+constexpr size_t kScratchOffBytes = 4096;  // off[kPackMaxPtrs + 1] as int64, padded
+constexpr size_t kScratchFirstEntries = size_t(kNoAllocMaxElems / mc::kLookupElems) + 1;
+constexpr size_t kScratchBytes = (kScratchOffBytes + kScratchFirstEntries * sizeof(int32_t) + 255) / 256 * 256;
+static_assert((mc::kPackMaxPtrs + 1) * sizeof(int64_t) <= kScratchOffBytes, "offsets fit their slot");
+
+// Each GPU the library runs on holds its own copy of this array (about 4 MiB) until the process
+// ends.  In host code the name is only a handle for hipGetSymbolAddress: the address that kernels
+// and copies may use is the one that call returns, per device.
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[mc::kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int scratch_address(unsigned char** out) {
+    int dev = -1;
+    MC_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= mc::kMaxDevices) return MC_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        MC_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return MC_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+    return MC_OK;
+}
+
+struct OffBatch {
+    int64_t off[mc::kPackMaxPtrs + 1];
+};
+
+// Writes the n + 1 flat offsets and, for each of n_entries runs of kLookupElems flat elements, the
+// first tensor whose range ends after the run's first element (n when there is none).
+__global__ __launch_bounds__(kThreads) void noalloc_tables_kernel(OffBatch ob, int32_t n, int64_t* off_out,
+                                                                  int32_t* first_out, int64_t n_entries) {
+    __shared__ int64_t off[mc::kPackMaxPtrs + 1];
+    for (int t = int(threadIdx.x); t <= n; t += kThreads) off[t] = ob.off[t];
+    __syncthreads();
+    if (blockIdx.x == 0)
+        for (int t = int(threadIdx.x); t <= n; t += kThreads) off_out[t] = off[t];
+    const int64_t j = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (j >= n_entries) return;
+    const int64_t first = j * mc::kLookupElems;
+    // smallest t in [0, n] with t == n or off[t + 1] > first (off is non-decreasing)
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid + 1] > first) hi = mid; else lo = mid + 1;
+    }
+    first_out[j] = lo;
+}
+
+int run_noalloc(const mc_layout* L, void* const* tensors, void* flat, void* stream) {
+    if (!L || !tensors) return MC_ERR_INVALID_ARG;
+    // the limits come first: nothing of the GPU is touched for a layout that cannot be served
+    if (L->n > mc::kPackMaxPtrs || L->N > kNoAllocMaxElems) return MC_ERR_LIMIT;
+    if (L->N == 0) return MC_OK;
+    if (!flat) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(flat, 16)) return MC_ERR_ALIGN;
+    const uint64_t flat_bytes = uint64_t(L->N) * 4;
+    for (int32_t t = 0; t < L->n; ++t) {
+        const int64_t cnt = L->off[t + 1] - L->off[t];
+        if (cnt == 0) continue;
+        if (!tensors[t]) return MC_ERR_INVALID_ARG;
+        if (!mc::aligned(tensors[t], 4)) return MC_ERR_ALIGN;
+        if (mc::overlaps(tensors[t], uint64_t(cnt) * 4, flat, flat_bytes)) return MC_ERR_OVERLAP;
+    }
+    unsigned char* base = nullptr;
+    const int rc = scratch_address(&base);
+    if (rc != MC_OK) return rc;
+
+    mc::DeviceTables dt;
+    dt.off = reinterpret_cast<int64_t*>(base);
+    dt.tile_first = reinterpret_cast<int32_t*>(base + kScratchOffBytes);
+    dt.ready = true;
+    const int64_t n_entries = int64_t(L->tile_first.size());   // ceil(N / kLookupElems) + 1
+    if (size_t(n_entries) > kScratchFirstEntries) return MC_ERR_LIMIT;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    OffBatch ob;
+    for (int32_t t = 0; t <= L->n; ++t) ob.off[t] = L->off[t];
+    for (int32_t t = L->n + 1; t <= mc::kPackMaxPtrs; ++t) ob.off[t] = L->N;
+    const unsigned blocks = unsigned((n_entries + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(noalloc_tables_kernel, dim3(blocks), dim3(kThreads), 0, s, ob, L->n, dt.off, dt.tile_first,
+                       n_entries);
+    MC_HIP_TRY(hipGetLastError());
+
+    PtrBatch batch;
+    for (int32_t t = 0; t < L->n; ++t) batch.p[t] = tensors[t];
+    for (int32_t t = L->n; t < mc::kPackMaxPtrs; ++t) batch.p[t] = nullptr;
+    return launch_range<false>(L, &dt, batch, nullptr, flat, 0, L->n, s);
+}
+
 }  // namespace
 
 namespace mc {
@@ -312,6 +412,10 @@ int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream) 
 
 int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream) {
     return run<true>(L, tensors, const_cast<void*>(flat), stream);
+}
+
+int mc_pack_noalloc(const mc_layout* L, const void* const* tensors, void* flat, void* stream) {
+    return run_noalloc(L, const_cast<void* const*>(tensors), flat, stream);
 }
 
 int mc_pack_set(mc_layout* L, const mc_tensor_set* tensors, void* flat, void* stream) {

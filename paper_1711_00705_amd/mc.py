@@ -20,7 +20,10 @@ ERR_ALIGN = -2
 ERR_OVERLAP = -3
 ERR_ALLOC = -4
 ERR_HIP = -5
+ERR_LIMIT = -6
 MAX_P = 32
+NOALLOC_MAX_TENSORS = 256
+NOALLOC_MAX_ELEMS = 1 << 28
 COLOUR_ALIGN_ELEMS = 256
 OPT_RU_UNROLL = 1
 OPT_RU_NONTEMPORAL = 2
@@ -46,6 +49,7 @@ SIGNATURES = {
     "mc_layout_colour_bounds": (ctypes.c_int, [_vp, _i64p]),
     "mc_pack": (ctypes.c_int, [_vp, _vpp, _vp, _vp]),
     "mc_unpack": (ctypes.c_int, [_vp, _vp, _vpp, _vp]),
+    "mc_pack_noalloc": (ctypes.c_int, [_vp, _vpp, _vp, _vp]),
     "mc_reduce_update": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp,
                                         ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
     "mc_colour_trees": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, _i32p]),
@@ -206,6 +210,13 @@ def pack(layout: Layout, tensor_ptrs: Sequence[Optional[int]], flat_ptr: Optiona
     if _count(tensor_ptrs) != layout.n:
         raise ValueError("need one pointer per tensor of the layout")
     _check(lib.mc_pack(layout.handle, _ptr_table(tensor_ptrs), flat_ptr, stream or None), "mc_pack")
+
+
+def pack_noalloc(layout: Layout, tensor_ptrs: Sequence[Optional[int]], flat_ptr: Optional[int],
+                 stream: int = 0) -> None:
+    if _count(tensor_ptrs) != layout.n:
+        raise ValueError("need one pointer per tensor of the layout")
+    _check(lib.mc_pack_noalloc(layout.handle, _ptr_table(tensor_ptrs), flat_ptr, stream or None), "mc_pack_noalloc")
 
 
 def unpack(layout: Layout, flat_ptr: Optional[int], tensor_ptrs: Sequence[Optional[int]], stream: int = 0) -> None:

@@ -30,8 +30,30 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_error_strings():
-    for code in (0, -1, -2, -3, -4, -5, -99):
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert isinstance(mc.strerror(code), str) and mc.strerror(code)
+    assert len({mc.strerror(code) for code in (0, -1, -2, -3, -4, -5, -6, -99)}) == 8
+
+
+def test_pack_noalloc_rejects_before_touching_the_gpu():
+    """The capacity limits and the argument checks of mc_pack_noalloc come before its first HIP
+    call, so they can be exercised without a GPU."""
+    f = mc.lib.mc_pack_noalloc
+    too_many = mc.Layout([4] * (mc.NOALLOC_MAX_TENSORS + 1), 2)
+    tab = mc.ptr_table([0x1000] * too_many.n)
+    assert f(too_many.handle, tab, 0x10000, None) == mc.ERR_LIMIT
+    too_long = mc.Layout([mc.NOALLOC_MAX_ELEMS, 1], 4)
+    assert f(too_long.handle, mc.ptr_table([0x1000, 0x2000]), 0x10000, None) == mc.ERR_LIMIT
+    L = mc.Layout([8, 0, 8], 2)
+    assert f(None, mc.ptr_table([0x1000, None, 0x2000]), 0x10000, None) == mc.ERR_INVALID_ARG
+    assert f(L.handle, None, 0x10000, None) == mc.ERR_INVALID_ARG
+    assert f(L.handle, mc.ptr_table([0x1000, None, 0x2000]), None, None) == mc.ERR_INVALID_ARG
+    assert f(L.handle, mc.ptr_table([0x1000, None, 0x2000]), 0x10008, None) == mc.ERR_ALIGN
+    assert f(L.handle, mc.ptr_table([0x1000, None, None]), 0x10000, None) == mc.ERR_INVALID_ARG
+    assert f(L.handle, mc.ptr_table([0x1002, None, 0x2000]), 0x10000, None) == mc.ERR_ALIGN
+    assert f(L.handle, mc.ptr_table([0x10010, None, 0x2000]), 0x10000, None) == mc.ERR_OVERLAP
+    empty = mc.Layout([0, 0], 3)
+    assert f(empty.handle, mc.ptr_table([None, None]), None, None) == mc.OK
 
 
 LAYOUT_CASES = [([5], 1), ([0], 3), ([0, 0, 7, 0], 2), ([256], 1), ([257], 2), ([1024], 4),
