@@ -300,7 +300,7 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     if args.unroll:
-        mc.set_option(mc.OPT_RU_UNROLL, args.unroll)
+        mc.set_option(mc.OPT_RU_SHAPE, args.unroll)
     if args.alternate_sweep >= 0:
         mc.set_option(mc.OPT_ALTERNATE_SWEEP, args.alternate_sweep)
     if args.state_store_sc1 >= 0:

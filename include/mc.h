@@ -25,9 +25,14 @@
  *     the call and never retained.
  *   - mc_pack / mc_unpack / mc_reduce_update validate their arguments on the host BEFORE
  *     any launch; on error no output is touched.  On success they enqueue work on `stream`
- *     (NULL = the default stream) and return without synchronising.
- *   - A layout is immutable after mc_layout_prepare and may then be used from several host
- *     threads and streams at once.
+ *     (NULL = the default stream) and return without synchronising.  The exceptions, which
+ *     allocate device memory and copy synchronously: mc_layout_prepare, mc_tensor_set_create, and
+ *     the first mc_pack / mc_unpack / mc_pack_set / mc_unpack_set / mc_fused_step(_ex) on a device
+ *     for a layout that was not prepared there.  Prepare layouts and create tensor sets at set-up
+ *     and no later call allocates, copies or blocks.
+ *   - After mc_layout_prepare a layout's tables never change and it may be used from several host
+ *     threads and streams at once.  (One call counter inside it does change: it only picks the
+ *     direction in which MC_SWEEP_AUTO calls walk the payload, see mc_update_spec.)
  *   - What validation cannot see: a device pointer carries no length.  Every flat buffer of a
  *     call must hold the layout's N elements and tensor t of a tensor list numel[t] elements,
  *     all resident on the current device.  Null pointers, misalignment and overlap are
@@ -140,7 +145,8 @@ int mc_pack_noalloc(const mc_layout* L, const void* const* tensors, void* flat, 
  *           permutation of 0..P-1.  NULL = identity for every colour.
  * grad_out: device N fp32 or NULL; weights, momentum: device N fp32, updated in place.
  * Errors: MC_ERR_INVALID_ARG (NULL, P < 1, P > MC_MAX_P, bad order row), MC_ERR_ALIGN,
- * MC_ERR_OVERLAP (any two of contrib[*], grad_out, weights, momentum overlap), MC_ERR_HIP. */
+ * MC_ERR_OVERLAP (grad_out, weights or momentum overlaps another buffer of the call; the
+ * contributions are only read, so the same buffer may be given twice), MC_ERR_HIP. */
 int mc_reduce_update(const mc_layout* L, const void* const* contrib, int32_t P,
                      const int32_t* order, void* grad_out, void* weights, void* momentum,
                      float lr, float mu, float wd, void* stream);
@@ -255,6 +261,18 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
  *   mc_reduce_update; nesterov = 1 applies the look-ahead form  w' = w - lr*(d + mu*v')  with the
  *   same d and v' (the paper names no variant; the Torch ResNet recipe it builds on uses this
  *   one).  Any other value: MC_ERR_INVALID_ARG.
+ *   state_policy and sweep change how memory is walked, never a result:
+ *   state_policy (MC_STATE_*): how weights and momentum are treated in the caches.  RESIDENT keeps
+ *     them cached (fastest when steps run back to back on a model whose weights + momentum fit the
+ *     256 MB memory-side cache); STREAMING treats them like the contributions (fastest when they
+ *     cannot be cached anyway: a forward / backward pass ran since the last step, as in Section 3,
+ *     Algorithm 1, or they exceed the cache).  DEFAULT defers to MC_OPT_STATE_POLICY.
+ *   sweep (MC_SWEEP_*): the direction in which a whole-payload call walks the payload.  FORWARD /
+ *     BACKWARD fix it (a caller that captures steps into graphs captures one of each and
+ *     alternates them).  AUTO: calls with resident state larger than the memory-side cache
+ *     alternate, using a per-layout call counter (so the direction depends on the calls made so
+ *     far on that layout, from any thread); all other calls walk forward.
+ *   A spec must be zero-initialised apart from the fields set (unknown values: MC_ERR_INVALID_ARG).
  * mc_reduce_update_ex: the most general form of mc_reduce_update: n_terms / do_update both NULL or
  *   both given (as in _roles), range as in _range with elem_end < 0 meaning N.
  * mc_fused_step_ex: mc_fused_step with a spec and with per-colour roles: n_terms / do_update both
@@ -263,10 +281,14 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
  *   as tensor sets this is a rank's whole step in a tree Allreduce without any staging copy.
  * mc_hyper_write: enqueues on `stream` a write of {lr, mu, wd} to hyper_dev (a one-thread kernel;
  *   no host memory is read after the call returns, nothing synchronises). */
+enum { MC_STATE_DEFAULT = 0, MC_STATE_RESIDENT = 1, MC_STATE_STREAMING = 2 };
+enum { MC_SWEEP_AUTO = 0, MC_SWEEP_FORWARD = 1, MC_SWEEP_BACKWARD = 2 };
 typedef struct mc_update_spec {
     float lr, mu, wd;
     const float* hyper_dev;
     int32_t nesterov;
+    int32_t state_policy;
+    int32_t sweep;
 } mc_update_spec;
 int mc_reduce_update_ex(const mc_layout* L, const void* const* contrib, int32_t P,
                         const int32_t* order, const int32_t* n_terms, const uint8_t* do_update,
@@ -304,24 +326,27 @@ int mc_last_hip_error(void);           /* raw hipError_t of this thread's last M
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  * Returns MC_ERR_INVALID_ARG for an unknown option or a value outside its range. */
 enum {
-    MC_OPT_RU_UNROLL = 1,          /* 16-byte vectors per thread per tile in reduce_update and
-                                      fused_step: 1 or 2; 0 (default) = chosen from the size */
-    MC_OPT_RU_NONTEMPORAL = 2,     /* 0 / 1: streaming (non-temporal) loads of the contributions
-                                      and store of grad_out.  Weights and momentum always use
-                                      the normal policy so that they stay cached. */
+    MC_OPT_RU_SHAPE = 1,           /* workgroup shape of reduce_update and fused_step: 1 = 64 threads x
+                                      one 16-byte vector, 2 = 256 threads x two vectors; 0 (default) =
+                                      chosen per launch from the size, the term count and the state
+                                      policy */
+    MC_OPT_STATE_POLICY = 2,       /* what MC_STATE_DEFAULT means: MC_STATE_RESIDENT, MC_STATE_STREAMING,
+                                      or 0 (default) = resident when weights + momentum fit the 256 MB
+                                      memory-side cache, else streaming */
     MC_OPT_PACK_NONTEMPORAL = 3,   /* pack/unpack: bit 0 streaming access to the per-layer
                                       tensors, bit 1 streaming access to the flat payload
                                       (non-temporal loads, write-through stores) */
-    MC_OPT_STATE_STORE_SC1 = 4,    /* 0 / 1: full tiles store updated weights and momentum with the
-                                      agent-scope (write-through) bit */
-    MC_OPT_ALTERNATE_SWEEP = 5,    /* 0 / 1: when weights + momentum exceed the 256 MB memory-side
-                                      cache, successive whole-payload update calls on a layout walk
-                                      the payload in opposite directions, so that the state written
-                                      last is read first */
-    MC_OPT_XCD_RUN = 6             /* 0..64: workgroups are dealt to the chip's 8 dies round-robin;
-                                      with a value r > 1 every kernel permutes its tiles so that each
-                                      die walks r consecutive tiles (neighbouring tiles then share one
-                                      L2).  0 or 1: tile = workgroup index. */
+    MC_OPT_STATE_STORE_SC1 = 4,    /* 0 / 1: resident-policy tiles store updated weights and momentum
+                                      with the agent-scope (write-through) bit */
+    MC_OPT_ALTERNATE_SWEEP = 5,    /* 0 / 1: whether MC_SWEEP_AUTO alternates at all */
+    MC_OPT_XCD_RUN = 6,            /* 0..64: workgroups are dealt to the chip's 8 dies round-robin;
+                                      with a value r > 1 the reduce_update and fused_step kernels
+                                      permute their tiles so that each die walks r consecutive tiles
+                                      (neighbouring tiles then share one L2).  0 or 1: tile =
+                                      workgroup index. */
+    MC_OPT_XCD_RUN_PACK = 7,       /* the same for mc_pack / mc_pack_set; -1 (default) = chosen from the
+                                      payload size */
+    MC_OPT_XCD_RUN_UNPACK = 8      /* the same for mc_unpack / mc_unpack_set */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

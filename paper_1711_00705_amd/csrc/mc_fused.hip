@@ -25,15 +25,17 @@
 
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kMaxSegs = 32;
 constexpr int kPtrSlots = 256;
 
 struct FusedArgs {
-    const float* const* x[kPtrSlots];   // x[s*np + q]: pointer table of the q-th term of segment s
+    const float* const* x[kPtrSlots];   // x[x_begin[s] + q]: pointer table of the q-th term of segment s
     int64_t lo[kMaxSegs];
     int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
+    int16_t x_begin[kMaxSegs];
+    uint8_t n_terms[kMaxSegs];      // terms of segment s (read by per-segment launches only)
+    uint8_t seg_update[kMaxSegs];   // does segment s apply the update? (per-segment launches only)
     int32_t n_segs;
     int32_t reverse;                // walk the launch's tiles from the last to the first
     int32_t xcd_run;                // consecutive tiles per die (see mc_tiles.h); <= 1: plain
@@ -81,6 +83,14 @@ __device__ __forceinline__ bool aligned16(const void* p) {
     return (reinterpret_cast<uintptr_t>(p) & 15) == 0;
 }
 
+// What a launch does with the sum.
+enum : int {
+    kSumOnly = 0,      // write it to g (colours of which the rank is a leaf or inner node)
+    kUpdateAndG = 1,   // write it to g and apply the SGD step
+    kUpdateOnly = 2,   // apply the SGD step, g is not wanted
+    kPerSegment = 3    // each segment has its own number of terms and its own update flag
+};
+
 // One element: the colour's sum in sequence, the update, the stores.
 template <bool HAS_G, bool UPDATE>
 __device__ __forceinline__ void one_element(const float* const* const* xs, int np, int32_t t, int64_t r,
@@ -104,7 +114,8 @@ __device__ __forceinline__ void one_element(const float* const* const* xs, int n
 // gp the matching position in the flat gradient.  SHIFTED: that boundary is not the tile's first
 // element, so gp is not 16-byte aligned (g is stored word by word) and the tile has one vector
 // less (n_vec); the few elements before and after the vectors are done by the caller.
-template <int P, int U, bool HAS_G, bool UPDATE, bool NT, bool SHIFTED>
+// SS: weights and momentum are streamed instead of kept resident (see mc_update.h).
+template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS, bool SHIFTED>
 __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int np, int32_t t0, int64_t rel,
                                              float* wp, float* vp, float* gp, int n_vec,
                                              const mc::Hyper& hp) {
@@ -112,7 +123,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
     bool on[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int jv = u * kThreads + int(threadIdx.x);
+        const int jv = u * THREADS + int(threadIdx.x);
         on[u] = !SHIFTED || jv < n_vec;
         j[u] = int64_t(jv) * 4;
     }
@@ -124,13 +135,13 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
             const float* xq = xs[q][t0] + rel;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (on[u]) t[q][u] = load4<NT>(xq + j[u]);
+                if (on[u]) t[q][u] = load4<true>(xq + j[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (UPDATE && on[u]) {
-                wv[u] = load4<false>(wp + j[u]);
-                vv[u] = load4<false>(vp + j[u]);
+                wv[u] = mc::load_state<SS>(wp + j[u]);
+                vv[u] = mc::load_state<SS>(vp + j[u]);
             }
         }
 #pragma unroll
@@ -149,10 +160,10 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
         for (int u = 0; u < U; ++u) {
             if (on[u]) {
                 if (UPDATE) {
-                    wv[u] = load4<false>(wp + j[u]);
-                    vv[u] = load4<false>(vp + j[u]);
+                    wv[u] = mc::load_state<SS>(wp + j[u]);
+                    vv[u] = mc::load_state<SS>(vp + j[u]);
                 }
-                acc[u] = load4<NT>(xs[0][t0] + rel + j[u]);
+                acc[u] = load4<true>(xs[0][t0] + rel + j[u]);
             }
         }
         // Four terms' loads are issued before their adds (more bytes in flight); the adds still
@@ -165,7 +176,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
                 const float* xq = xs[q + r][t0] + rel;
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (on[u]) t[r][u] = load4<NT>(xq + j[u]);
+                    if (on[u]) t[r][u] = load4<true>(xq + j[u]);
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
@@ -182,7 +193,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (on[u]) {
-                    const float4 t = load4<NT>(xq + j[u]);
+                    const float4 t = load4<true>(xq + j[u]);
                     acc[u].x = acc[u].x + t.x;
                     acc[u].y = acc[u].y + t.y;
                     acc[u].z = acc[u].z + t.z;
@@ -202,7 +213,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
                 st1(gq + 2, acc[u].z);
                 st1(gq + 3, acc[u].w);
             } else {
-                store4<NT>(gp + j[u], acc[u]);
+                store4<true>(gp + j[u], acc[u]);
             }
         }
         if (UPDATE) {
@@ -210,40 +221,22 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
             mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
             mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
             mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-            mc::store_state(wp + j[u], wv[u], hp.state_store_sc1);
-            mc::store_state(vp + j[u], vv[u], hp.state_store_sc1);
+            mc::store_state<SS>(wp + j[u], wv[u], hp.state_store_sc1);
+            mc::store_state<SS>(vp + j[u], vv[u], hp.state_store_sc1);
         }
     }
 }
 
-// P > 0: compile-time number of terms; P == 0: run-time count in Prt.
+// One tile [base, end) of a segment whose first element lies in tensor t0 = [t0_begin, t0_end).
+// P > 0: compile-time number of terms; P == 0: run-time count np.
 // UPDATE: the SGD step follows the sum; otherwise only the sum is written to g (the colours of
 // which this rank is a leaf or inner node) and weights / momentum are never touched.
-template <int P, int U, bool HAS_G, bool UPDATE, bool NT>
-__global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int Prt) {
-    static_assert(HAS_G || UPDATE, "a launch must produce something");
-    constexpr int kTile = kThreads * 4 * U;
-    static_assert(kTile % mc::kLookupElems == 0, "tiles start on lookup entries");
-    const int np = P > 0 ? P : Prt;
-    const mc::Hyper hp = mc::resolve(a.up);
-
-    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
-    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
-    int s = 0;
-    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
-    const int64_t lo = a.lo[s];
-    const int64_t hi = a.hi[s];
-    const int64_t base = lo + int64_t(blk - a.first_block[s]) * kTile;  // multiple of 256
-    const int64_t end = base + kTile < hi ? base + kTile : hi;
-    const float* const* const* xs = a.x + s * np;
-
-    // The tensor holding the tile's first element (block-uniform).  `base` is a multiple of the
-    // lookup granularity, so the table entry is that tensor itself: no scan of off[] is needed and
-    // the loads of its bounds and of the operands' base pointers do not wait for one another.
-    const int32_t t0 = a.first_tensor[base / mc::kLookupElems];
-    const int64_t t0_begin = a.off[t0];
-    const int64_t t0_end = a.off[t0 + 1];
-
+template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
+__device__ __forceinline__ void fused_tile(const FusedArgs& a, const float* const* const* xs, int np,
+                                           int64_t base, int64_t end, int32_t t0, int64_t t0_begin,
+                                           int64_t t0_end, const mc::Hyper& hp) {
+    static_assert(HAS_G || UPDATE, "a tile must produce something");
+    constexpr int kTile = THREADS * 4 * U;
     if (end - base == kTile && end <= t0_end) {
         // Whole tile inside tensor t0.  If every operand has the same offset from a 16-byte
         // boundary (all zero for a CNN payload; equal and non-zero after an odd-sized tensor,
@@ -255,15 +248,15 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
         bool same = !UPDATE || (misalignment(wp) == m && misalignment(vp) == m);
         for (int q = 1; q < np; ++q) same = same && misalignment(xs[q][t0] + rel) == m;
         if (same && m == 0) {
-            uniform_tile<P, U, HAS_G, UPDATE, NT, false>(xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
+            uniform_tile<P, U, THREADS, HAS_G, UPDATE, SS, false>(xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
             return;
         }
         if (same) {
             const int head = 4 - m;               // elements up to the operands' 16-byte boundary
             const int n_vec = kTile / 4 - 1;      // whole vectors after it
-            uniform_tile<P, U, HAS_G, UPDATE, NT, true>(xs, np, t0, rel + head, UPDATE ? wp + head : nullptr,
-                                                        UPDATE ? vp + head : nullptr, a.g + base + head,
-                                                        n_vec, hp);
+            uniform_tile<P, U, THREADS, HAS_G, UPDATE, SS, true>(xs, np, t0, rel + head, UPDATE ? wp + head : nullptr,
+                                                                 UPDATE ? vp + head : nullptr, a.g + base + head,
+                                                                 n_vec, hp);
             // the `head` elements before the vectors and the `4 - head` after them
             if (threadIdx.x < 4) {
                 const int e = int(threadIdx.x) < head ? int(threadIdx.x)
@@ -277,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
     // General tile: tensor boundaries, the ragged end of the segment, or operands whose
     // alignments differ.
     for (int u = 0; u < U; ++u) {
-        const int64_t i = base + (int64_t(u) * kThreads + threadIdx.x) * 4;
+        const int64_t i = base + (int64_t(u) * THREADS + threadIdx.x) * 4;
         if (i >= end) break;
         int32_t t = t0;
         while (a.off[t + 1] <= i) ++t;  // ends: i < end <= N == off[n]
@@ -286,9 +279,9 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
         if (vec && UPDATE) vec = aligned16(a.w[t] + rel) && aligned16(a.v[t] + rel);
         for (int q = 0; q < np && vec; ++q) vec = aligned16(xs[q][t] + rel);
         if (vec) {
-            float4 acc = load4<NT>(xs[0][t] + rel);
+            float4 acc = load4<true>(xs[0][t] + rel);
             for (int q = 1; q < np; ++q) {
-                const float4 x = load4<NT>(xs[q][t] + rel);
+                const float4 x = load4<true>(xs[q][t] + rel);
                 acc.x = acc.x + x.x;
                 acc.y = acc.y + x.y;
                 acc.z = acc.z + x.z;
@@ -317,41 +310,108 @@ __global__ __launch_bounds__(kThreads) void fused_step_kernel(FusedArgs a, int P
     }
 }
 
-template <int P, int U>
-void launch_variant(bool update, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
-    const dim3 grid(blocks), block(kThreads);
-#define MC_FUSED_LAUNCH(G, UPD, NT) \
-    hipLaunchKernelGGL((fused_step_kernel<P, U, G, UPD, NT>), grid, block, 0, s, a, Prt)
-    if (!update) {
-        if (nt) MC_FUSED_LAUNCH(true, false, true); else MC_FUSED_LAUNCH(true, false, false);
-    } else if (a.g) {
-        if (nt) MC_FUSED_LAUNCH(true, true, true); else MC_FUSED_LAUNCH(true, true, false);
+// A per-segment launch picks the compile-time body of the segment's term count.
+template <int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
+__device__ __forceinline__ void fused_tile_any(const FusedArgs& a, const float* const* const* xs, int np,
+                                               int64_t base, int64_t end, int32_t t0, int64_t t0_begin,
+                                               int64_t t0_end, const mc::Hyper& hp) {
+#define MC_FUSED_CASE(N) \
+    case N: fused_tile<N, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp); break
+    switch (np) {
+        MC_FUSED_CASE(1);
+        MC_FUSED_CASE(2);
+        MC_FUSED_CASE(3);
+        MC_FUSED_CASE(4);
+        MC_FUSED_CASE(5);
+        MC_FUSED_CASE(6);
+        MC_FUSED_CASE(7);
+        MC_FUSED_CASE(8);
+        default: fused_tile<0, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp); break;
+    }
+#undef MC_FUSED_CASE
+}
+
+template <int P, int U, int THREADS, int MODE, bool SS>
+__global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Prt) {
+    constexpr int kTile = THREADS * 4 * U;
+    static_assert(kTile % mc::kLookupElems == 0, "tiles start on lookup entries");
+    const mc::Hyper hp = mc::resolve(a.up);
+
+    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
+    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
+    int s = 0;
+    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
+    const int64_t hi = a.hi[s];
+    const int64_t base = a.lo[s] + int64_t(blk - a.first_block[s]) * kTile;  // multiple of 256
+    const int64_t end = base + kTile < hi ? base + kTile : hi;
+    const float* const* const* xs = a.x + a.x_begin[s];
+
+    // The tensor holding the tile's first element (block-uniform).  `base` is a multiple of the
+    // lookup granularity, so the table entry is that tensor itself: no scan of off[] is needed and
+    // the loads of its bounds and of the operands' base pointers do not wait for one another.
+    const int32_t t0 = a.first_tensor[base / mc::kLookupElems];
+    const int64_t t0_begin = a.off[t0];
+    const int64_t t0_end = a.off[t0 + 1];
+
+    if (MODE == kPerSegment) {
+        const int np = a.n_terms[s];
+        if (a.seg_update[s]) {
+            if (a.g)
+                fused_tile_any<U, THREADS, true, true, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp);
+            else
+                fused_tile_any<U, THREADS, false, true, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp);
+        } else {
+            fused_tile_any<U, THREADS, true, false, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp);
+        }
     } else {
-        if (nt) MC_FUSED_LAUNCH(false, true, true); else MC_FUSED_LAUNCH(false, true, false);
+        const int np = P > 0 ? P : Prt;
+        fused_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(a, xs, np, base, end, t0, t0_begin,
+                                                                             t0_end, hp);
+    }
+}
+
+template <int P, int U, int T>
+void launch_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
+    const dim3 grid(blocks), block(T);
+#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_step_kernel<P, U, T, MODE, SS>), grid, block, 0, s, a, Prt)
+    switch (mode) {
+        case kSumOnly: MC_FUSED_LAUNCH(kSumOnly, false); break;   // state is not touched: one policy
+        case kUpdateAndG: if (ss) MC_FUSED_LAUNCH(kUpdateAndG, true); else MC_FUSED_LAUNCH(kUpdateAndG, false); break;
+        default: if (ss) MC_FUSED_LAUNCH(kUpdateOnly, true); else MC_FUSED_LAUNCH(kUpdateOnly, false); break;
     }
 #undef MC_FUSED_LAUNCH
 }
 
 template <int P>
-void launch_unroll(int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
-    if (unroll == 1)
-        launch_variant<P, 1>(update, nt, blocks, s, a, Prt);
+void launch_shape(mc::Shape shape, int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
+    if (shape.threads == 64)
+        launch_mode<P, 1, 64>(mode, ss, blocks, s, a, Prt);
     else
-        launch_variant<P, 2>(update, nt, blocks, s, a, Prt);
+        launch_mode<P, 2, 256>(mode, ss, blocks, s, a, Prt);
 }
 
-void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const FusedArgs& a) {
+// A launch whose segments all add P terms and agree on updating.
+void launch(int P, mc::Shape shape, int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
     switch (P) {
-        case 1: launch_unroll<1>(unroll, update, nt, blocks, s, a, P); break;
-        case 2: launch_unroll<2>(unroll, update, nt, blocks, s, a, P); break;
-        case 3: launch_unroll<3>(unroll, update, nt, blocks, s, a, P); break;
-        case 4: launch_unroll<4>(unroll, update, nt, blocks, s, a, P); break;
-        case 5: launch_unroll<5>(unroll, update, nt, blocks, s, a, P); break;
-        case 6: launch_unroll<6>(unroll, update, nt, blocks, s, a, P); break;
-        case 7: launch_unroll<7>(unroll, update, nt, blocks, s, a, P); break;
-        case 8: launch_unroll<8>(unroll, update, nt, blocks, s, a, P); break;
-        default: launch_unroll<0>(unroll, update, nt, blocks, s, a, P); break;
+        case 1: launch_shape<1>(shape, mode, ss, blocks, s, a, P); break;
+        case 2: launch_shape<2>(shape, mode, ss, blocks, s, a, P); break;
+        case 3: launch_shape<3>(shape, mode, ss, blocks, s, a, P); break;
+        case 4: launch_shape<4>(shape, mode, ss, blocks, s, a, P); break;
+        case 5: launch_shape<5>(shape, mode, ss, blocks, s, a, P); break;
+        case 6: launch_shape<6>(shape, mode, ss, blocks, s, a, P); break;
+        case 7: launch_shape<7>(shape, mode, ss, blocks, s, a, P); break;
+        case 8: launch_shape<8>(shape, mode, ss, blocks, s, a, P); break;
+        default: launch_shape<0>(shape, mode, ss, blocks, s, a, P); break;
     }
+}
+
+// A launch whose segments differ in term count or update flag (always 64 threads x 1 vector).
+void launch_per_segment(bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
+    const dim3 grid(blocks), block(64);
+    if (ss)
+        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, true>), grid, block, 0, s, a, 0);
+    else
+        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, false>), grid, block, 0, s, a, 0);
 }
 
 // Do two sorted lists of [begin, end) spans intersect anywhere?
@@ -442,10 +502,10 @@ int mc_tensor_set_destroy(mc_tensor_set* S) {
 static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
                           const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
                           const mc_tensor_set* weights, const mc_tensor_set* momentum,
-                          const mc::UpdateParams& up, void* stream) {
+                          const mc::UpdatePlan& plan, void* stream) {
     if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
     if ((n_terms == nullptr) != (do_update == nullptr)) return MC_ERR_INVALID_ARG;
-    if (up.hyper && !mc::aligned(up.hyper, 4)) return MC_ERR_ALIGN;
+    if (plan.up.hyper && !mc::aligned(plan.up.hyper, 4)) return MC_ERR_ALIGN;
     if ((weights && weights->layout != L) || (momentum && momentum->layout != L)) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
         if (!contrib[p] || contrib[p]->layout != L) return MC_ERR_INVALID_ARG;
@@ -459,13 +519,21 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             }
         }
     }
-    bool any_update = false, any_sum_only = false;
+    auto terms = [&](int32_t c) { return n_terms ? n_terms[c] : P; };
+    auto updates = [&](int32_t c) { return do_update ? do_update[c] != 0 : true; };
+    auto active = [&](int32_t c) { return terms(c) > 0 && L->bounds[c + 1] > L->bounds[c]; };
+    bool any_update = false, any_sum_only = false, uniform = true;
+    int32_t first_active = -1;
+    int max_terms = 0;
     for (int32_t c = 0; c < L->k; ++c) {
         if (n_terms && (n_terms[c] < 0 || n_terms[c] > P)) return MC_ERR_INVALID_ARG;
-        if ((n_terms && n_terms[c] == 0) || L->bounds[c + 1] == L->bounds[c]) continue;
-        if (!do_update || do_update[c]) any_update = true; else any_sum_only = true;
+        if (!active(c)) continue;
+        if (updates(c)) any_update = true; else any_sum_only = true;
+        max_terms = std::max(max_terms, int(terms(c)));
+        if (first_active < 0) first_active = c;
+        else if (terms(c) != terms(first_active) || updates(c) != updates(first_active)) uniform = false;
     }
-    if (!any_update && !any_sum_only) return MC_OK;
+    if (first_active < 0) return MC_OK;
     if (any_update && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
     if (any_sum_only && !grad_out) return MC_ERR_INVALID_ARG;
     if (grad_out && !mc::aligned(grad_out, 16)) return MC_ERR_ALIGN;
@@ -496,74 +564,71 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     for (int32_t p = 0; p < P; ++p)
         if (contrib[p]->device != dev) return MC_ERR_INVALID_ARG;
 
-    const int unroll = mc::unroll_for(L->N);
-    const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
-    const int64_t tile = int64_t(kThreads) * 4 * unroll;
+    const bool ss = any_update && mc::stream_state(L, plan.state_policy);
+    // Launches that mix term counts or update flags use the one-wavefront shape.
+    const mc::Shape shape = uniform ? mc::shape_for(L->N, max_terms, ss) : mc::Shape{64, 1};
+    const int64_t tile = shape.tile();
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     FusedArgs a;
-    a.reverse = (!n_terms && mc::sweep_reversed(L)) ? 1 : 0;   // role calls come several to a step
+    // Only the plain whole-payload step alternates by itself: role calls come several to a step.
+    a.reverse = mc::sweep_reversed(L, (n_terms && plan.sweep == MC_SWEEP_AUTO) ? MC_SWEEP_FORWARD : plan.sweep, ss) ? 1 : 0;
     a.xcd_run = mc::option(MC_OPT_XCD_RUN);
     a.w = weights ? reinterpret_cast<float* const*>(weights->d_ptrs) : nullptr;
     a.v = momentum ? reinterpret_cast<float* const*>(momentum->d_ptrs) : nullptr;
     a.g = static_cast<float*>(grad_out);
     a.off = dt->off;
     a.first_tensor = dt->tile_first;
-    a.up = up;
+    a.up = plan.up;
 
-    // Colours that add the same number of terms and agree on updating share launches (at most two
-    // such classes for a real rank; one for the uniform call).  `done` marks colours launched.
-    std::vector<uint8_t> done(size_t(L->k), 0);
-    for (int32_t c0 = 0; c0 < L->k; ++c0) {
-        if (done[c0]) continue;
-        const int32_t cnt = n_terms ? n_terms[c0] : P;
-        const bool upd = do_update ? do_update[c0] != 0 : true;
-        if (cnt == 0 || L->bounds[c0 + 1] == L->bounds[c0]) {
-            done[c0] = 1;
-            continue;
-        }
-        const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / cnt);
-        int32_t c = c0;
-        while (c < L->k) {
-            int ns = 0;
-            int64_t blocks = 0;
-            a.first_block[0] = 0;
-            for (; c < L->k && ns < segs_per_launch; ++c) {
-                if (done[c]) continue;
-                const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
-                const int32_t cc = n_terms ? n_terms[c] : P;
-                const bool cu = do_update ? do_update[c] != 0 : true;
-                if (cc == 0 || hi == lo) {
-                    done[c] = 1;
-                    continue;
-                }
-                if (cc != cnt || cu != upd) continue;  // another class: a later pass takes it
-                const int64_t nblk = (hi - lo + tile - 1) / tile;
-                if (blocks + nblk > 0x7fffffff) {
-                    if (ns == 0) return MC_ERR_INVALID_ARG;
-                    break;
-                }
-                a.lo[ns] = lo;
-                a.hi[ns] = hi;
-                for (int32_t q = 0; q < cnt; ++q) {
-                    const int32_t src = order ? order[size_t(c) * P + q] : q;
-                    a.x[ns * cnt + q] = reinterpret_cast<const float* const*>(contrib[src]->d_ptrs);
-                }
-                blocks += nblk;
-                a.first_block[ns + 1] = int32_t(blocks);
-                done[c] = 1;
-                ++ns;
+    // Colours in index order, as many per launch as the segment and pointer slots hold: one launch
+    // for any realistic call, whatever the mix of roles.
+    int32_t c = 0;
+    while (c < L->k) {
+        int ns = 0, slots = 0;
+        int64_t blocks = 0;
+        a.first_block[0] = 0;
+        for (; c < L->k && ns < kMaxSegs; ++c) {
+            if (!active(c)) continue;
+            const int32_t cnt = terms(c);
+            if (slots + cnt > kPtrSlots) break;
+            const int64_t lo = L->bounds[c], hi = L->bounds[c + 1];
+            const int64_t nblk = (hi - lo + tile - 1) / tile;
+            if (blocks + nblk > 0x7fffffff) {
+                if (ns == 0) return MC_ERR_INVALID_ARG;
+                break;
             }
-            if (ns == 0) break;
-            for (int i = ns * cnt; i < kPtrSlots; ++i) a.x[i] = nullptr;
-            for (int i = ns; i < kMaxSegs; ++i) {
-                a.lo[i] = a.hi[i] = 0;
-                a.first_block[i + 1] = a.first_block[ns];
+            a.lo[ns] = lo;
+            a.hi[ns] = hi;
+            a.x_begin[ns] = int16_t(slots);
+            a.n_terms[ns] = uint8_t(cnt);
+            a.seg_update[ns] = updates(c) ? 1 : 0;
+            for (int32_t q = 0; q < cnt; ++q) {
+                const int32_t src = order ? order[size_t(c) * P + q] : q;
+                a.x[slots + q] = reinterpret_cast<const float* const*>(contrib[src]->d_ptrs);
             }
-            a.n_segs = ns;
-            launch(cnt, unroll, upd, nt, unsigned(blocks), s, a);
-            MC_HIP_TRY(hipGetLastError());
+            slots += cnt;
+            blocks += nblk;
+            a.first_block[ns + 1] = int32_t(blocks);
+            ++ns;
         }
+        if (ns == 0) break;
+        for (int i = slots; i < kPtrSlots; ++i) a.x[i] = nullptr;
+        for (int i = ns; i < kMaxSegs; ++i) {
+            a.lo[i] = a.hi[i] = 0;
+            a.x_begin[i] = 0;
+            a.n_terms[i] = 0;
+            a.seg_update[i] = 0;
+            a.first_block[i + 1] = a.first_block[ns];
+        }
+        a.n_segs = ns;
+        if (uniform) {
+            const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
+            launch(terms(first_active), shape, mode, ss, unsigned(blocks), s, a);
+        } else {
+            launch_per_segment(ss, unsigned(blocks), s, a);
+        }
+        MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
 }
@@ -572,9 +637,9 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
 static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
                      const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
                      const mc_tensor_set* weights, const mc_tensor_set* momentum,
-                     const mc::UpdateParams& up, void* stream) {
+                     const mc::UpdatePlan& plan, void* stream) {
     try {
-        return fused_run_impl(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up, stream);
+        return fused_run_impl(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, plan, stream);
     } catch (const std::bad_alloc&) {
         return MC_ERR_ALLOC;
     }
@@ -583,25 +648,27 @@ static int fused_run(mc_layout* L, const mc_tensor_set* const* contrib, int32_t 
 int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
                   void* grad_out, const mc_tensor_set* weights, const mc_tensor_set* momentum,
                   float lr, float mu, float wd, void* stream) {
-    mc::UpdateParams up;
-    up.lr = lr;
-    up.mu = mu;
-    up.wd = wd;
-    up.hyper = nullptr;
-    up.nesterov = 0;
-    up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
+    mc::UpdatePlan plan;
+    plan.up.lr = lr;
+    plan.up.mu = mu;
+    plan.up.wd = wd;
+    plan.up.hyper = nullptr;
+    plan.up.nesterov = 0;
+    plan.up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
+    plan.state_policy = MC_STATE_DEFAULT;
+    plan.sweep = MC_SWEEP_AUTO;
     if (!weights || !momentum) return MC_ERR_INVALID_ARG;
-    return fused_run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, up, stream);
+    return fused_run(L, contrib, P, order, nullptr, nullptr, grad_out, weights, momentum, plan, stream);
 }
 
 int mc_fused_step_ex(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, const int32_t* order,
                      const int32_t* n_terms, const uint8_t* do_update, void* grad_out,
                      const mc_tensor_set* weights, const mc_tensor_set* momentum,
                      const mc_update_spec* spec, void* stream) {
-    mc::UpdateParams up;
-    const int rc = mc::update_params(spec, &up);
+    mc::UpdatePlan plan;
+    const int rc = mc::update_plan(spec, &plan);
     if (rc != MC_OK) return rc;
-    return fused_run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up, stream);
+    return fused_run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, plan, stream);
 }
 
 }  // extern "C"

@@ -42,8 +42,8 @@ struct mc_layout {
     std::vector<int64_t> off;         // n+1
     std::vector<int64_t> bounds;      // k+1
     std::vector<int32_t> tile_first;  // ceil(N / kLookupElems) + 1
-    // Parity of the next whole-payload update call: successive steps sweep the payload in opposite
-    // directions (see sweep_reversed()).
+    // Parity of the next whole-payload update call with automatic sweep direction (see
+    // sweep_reversed()): the one member that changes after prepare; it never affects a result.
     mutable std::atomic<uint32_t> sweep{0};
     std::mutex mu;                    // guards dev[] during prepare / destroy
     mc::DeviceTables dev[mc::kMaxDevices];
@@ -75,21 +75,40 @@ inline bool overlaps(const void* a, uint64_t na, const void* b, uint64_t nb) {
 // Returns the device tables of L for the current device, uploading them on first use.
 int device_tables(mc_layout* L, const DeviceTables** out);
 
-int option(int which);
-// Should this whole-payload update call walk the payload backwards?  Weights and momentum are the
-// only data that come back every step.  When they exceed the 256 MB memory-side cache, sweeping
-// the payload in the same direction every step evicts each line long before it is needed again;
-// alternating the direction makes the most recently written part the first to be read.  Measured on
-// a bare loop: 480 MB of state 5.8 -> 6.7 TB/s, 1.1 GB (VGG-16) 5.4 -> 5.8 TB/s; no gain when the
-// state fits, so smaller payloads keep one direction.  The result does not depend on the direction
-// (the step is elementwise).
-bool sweep_reversed(const mc_layout* L);
-// Vectors per thread per tile for a launch over `elems` elements (honours MC_OPT_RU_UNROLL).
-int unroll_for(int64_t elems);
+constexpr int kNoSuchOption = -1000;
+int option(int which);   // kNoSuchOption for an unknown option
+
+// Workgroup shape of the reduce_update / fused_step kernels for one launch.
+struct Shape {
+    int threads;   // 64 or 256
+    int vectors;   // 16-byte vectors per thread per tile: 1 or 2
+    int64_t tile() const { return int64_t(threads) * 4 * vectors; }
+};
+// 64 threads x 1 vector (one wavefront per workgroup) measured fastest everywhere the state is not
+// cache-resident, for small payloads and for more than four contributions (6-10 % over
+// 256 x 2 on cold ResNet-50- and VGG-16-sized steps); 256 x 2 is 1 % ahead on large back-to-back
+// steps with resident state and few contributions.  Honours MC_OPT_RU_SHAPE.
+Shape shape_for(int64_t elems, int n_terms, bool stream_state);
+
+// Cache treatment of weights and momentum for a call on layout L: `policy` is the caller's
+// MC_STATE_* value (MC_STATE_DEFAULT defers to MC_OPT_STATE_POLICY, whose automatic setting goes
+// by whether weights + momentum fit the 256 MB memory-side cache).
+bool stream_state(const mc_layout* L, int policy);
+
+// Should this whole-payload update call walk the payload backwards?  `sweep` is the caller's
+// MC_SWEEP_* value.  Automatic: weights and momentum are the only data that come back every step;
+// when they exceed the memory-side cache and are kept resident, sweeping in the same direction every
+// step evicts each line long before it is needed again, while alternating the direction makes the
+// most recently written part the first to be read (measured on a bare loop: 480 MB of state
+// 5.8 -> 6.7 TB/s, 1.1 GB 5.4 -> 5.8 TB/s; no gain when the state fits or is streamed).  The layout
+// keeps the parity of its automatic calls in one relaxed atomic counter -- the only thing in a
+// layout that changes after mc_layout_prepare, and it affects the order of the tiles, never a result.
+bool sweep_reversed(const mc_layout* L, int sweep, bool stream_state);
 
 struct UpdateParams;
-// Validates a caller's spec and converts it to the kernels' argument form.
-int update_params(const mc_update_spec* spec, UpdateParams* out);
+// A validated mc_update_spec: the kernels' argument form plus the host-side launch choices.
+struct UpdatePlan;
+int update_plan(const mc_update_spec* spec, UpdatePlan* out);
 
 }  // namespace mc
 

@@ -9,12 +9,17 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-std::atomic<int> g_ru_unroll{0};
-std::atomic<int> g_ru_nontemporal{1};
+std::atomic<int> g_ru_shape{0};
+std::atomic<int> g_state_policy{0};
 std::atomic<int> g_pack_nontemporal{3};
 std::atomic<int> g_state_store_sc1{1};
 std::atomic<int> g_alternate_sweep{1};
 std::atomic<int> g_xcd_run{0};
+std::atomic<int> g_xcd_run_pack{-1};
+std::atomic<int> g_xcd_run_unpack{0};
+
+// Capacity of the memory-side cache that sits between the L2s and HBM.
+constexpr int64_t kMemorySideCacheBytes = int64_t(256) << 20;
 
 }  // namespace
 
@@ -25,33 +30,44 @@ int hip_fail(hipError_t e) {
     return MC_ERR_HIP;
 }
 
-int unroll_for(int64_t elems) {
-    const int u = g_ru_unroll.load(std::memory_order_relaxed);
-    if (u != 0) return u;
-    // Two vectors per thread once the grid still has several rounds of workgroups per compute
-    // unit; one below that, where a finer grid fills the chip more evenly (measured: GoogLeNet
-    // 45.1 -> 43.3 us, ResNet-50 within 0.5 % either way).
-    return elems / 2048 >= 8192 ? 2 : 1;
+Shape shape_for(int64_t elems, int n_terms, bool stream_state) {
+    const int forced = g_ru_shape.load(std::memory_order_relaxed);
+    if (forced == 1) return Shape{64, 1};
+    if (forced == 2) return Shape{256, 2};
+    // 256 x 2 only where it measured ahead: many tiles, few contributions, state kept resident.
+    const bool large = elems / 2048 >= 8192;
+    if (large && n_terms <= 4 && !stream_state) return Shape{256, 2};
+    return Shape{64, 1};
 }
 
-bool sweep_reversed(const mc_layout* L) {
+bool stream_state(const mc_layout* L, int policy) {
+    if (policy == MC_STATE_DEFAULT) policy = g_state_policy.load(std::memory_order_relaxed);
+    if (policy == MC_STATE_RESIDENT) return false;
+    if (policy == MC_STATE_STREAMING) return true;
+    return L->N * 8 > kMemorySideCacheBytes;   // weights + momentum: 8 bytes per element
+}
+
+bool sweep_reversed(const mc_layout* L, int sweep, bool stream_state) {
+    if (sweep == MC_SWEEP_FORWARD) return false;
+    if (sweep == MC_SWEEP_BACKWARD) return true;
     if (!g_alternate_sweep.load(std::memory_order_relaxed)) return false;
-    // Only when weights + momentum (8 bytes per element) cannot stay in the 256 MB memory-side
-    // cache anyway; while they fit, a fixed direction measured 1-2 % faster.
-    constexpr int64_t kMemorySideCacheBytes = int64_t(256) << 20;
-    if (L->N * 8 <= kMemorySideCacheBytes) return false;
+    // Only resident state that cannot all stay in the cache gains from alternating; while it fits,
+    // a fixed direction measured 1-2 % faster, and streamed state leaves nothing behind to reuse.
+    if (stream_state || L->N * 8 <= kMemorySideCacheBytes) return false;
     return (L->sweep.fetch_add(1, std::memory_order_relaxed) & 1u) != 0;
 }
 
 int option(int which) {
     switch (which) {
-        case MC_OPT_RU_UNROLL: return g_ru_unroll.load(std::memory_order_relaxed);
-        case MC_OPT_RU_NONTEMPORAL: return g_ru_nontemporal.load(std::memory_order_relaxed);
+        case MC_OPT_RU_SHAPE: return g_ru_shape.load(std::memory_order_relaxed);
+        case MC_OPT_STATE_POLICY: return g_state_policy.load(std::memory_order_relaxed);
         case MC_OPT_PACK_NONTEMPORAL: return g_pack_nontemporal.load(std::memory_order_relaxed);
         case MC_OPT_STATE_STORE_SC1: return g_state_store_sc1.load(std::memory_order_relaxed);
         case MC_OPT_ALTERNATE_SWEEP: return g_alternate_sweep.load(std::memory_order_relaxed);
         case MC_OPT_XCD_RUN: return g_xcd_run.load(std::memory_order_relaxed);
-        default: return -1;
+        case MC_OPT_XCD_RUN_PACK: return g_xcd_run_pack.load(std::memory_order_relaxed);
+        case MC_OPT_XCD_RUN_UNPACK: return g_xcd_run_unpack.load(std::memory_order_relaxed);
+        default: return kNoSuchOption;
     }
 }
 
@@ -150,13 +166,13 @@ int mc_last_hip_error(void) { return g_last_hip_error; }
 
 int mc_set_option(int option, int value) {
     switch (option) {
-        case MC_OPT_RU_UNROLL:
+        case MC_OPT_RU_SHAPE:
             if (value != 0 && value != 1 && value != 2) return MC_ERR_INVALID_ARG;
-            g_ru_unroll.store(value, std::memory_order_relaxed);
+            g_ru_shape.store(value, std::memory_order_relaxed);
             return MC_OK;
-        case MC_OPT_RU_NONTEMPORAL:
-            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
-            g_ru_nontemporal.store(value, std::memory_order_relaxed);
+        case MC_OPT_STATE_POLICY:
+            if (value != 0 && value != MC_STATE_RESIDENT && value != MC_STATE_STREAMING) return MC_ERR_INVALID_ARG;
+            g_state_policy.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_PACK_NONTEMPORAL:
             if (value < 0 || value > 3) return MC_ERR_INVALID_ARG;
@@ -174,6 +190,14 @@ int mc_set_option(int option, int value) {
             if (value < 0 || value > 64) return MC_ERR_INVALID_ARG;
             g_xcd_run.store(value, std::memory_order_relaxed);
             return MC_OK;
+        case MC_OPT_XCD_RUN_PACK:
+            if (value < -1 || value > 64) return MC_ERR_INVALID_ARG;
+            g_xcd_run_pack.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_XCD_RUN_UNPACK:
+            if (value < -1 || value > 64) return MC_ERR_INVALID_ARG;
+            g_xcd_run_unpack.store(value, std::memory_order_relaxed);
+            return MC_OK;
         default:
             return MC_ERR_INVALID_ARG;
     }
@@ -182,7 +206,7 @@ int mc_set_option(int option, int value) {
 int mc_get_option(int option, int* value) {
     if (!value) return MC_ERR_INVALID_ARG;
     const int v = mc::option(option);
-    if (v < 0) return MC_ERR_INVALID_ARG;
+    if (v == mc::kNoSuchOption) return MC_ERR_INVALID_ARG;
     *value = v;
     return MC_OK;
 }

@@ -24,67 +24,56 @@
 
 namespace {
 
-constexpr int kThreads = 256;  // workgroup size
-constexpr int kMaxSegs = 32;     // colours per launch
-constexpr int kPtrSlots = 256;   // permuted contribution pointers per launch (kMaxSegs*P <= this)
+constexpr int kMaxSegs = 32;     // colour segments per launch
+constexpr int kPtrSlots = 256;   // permuted contribution pointers per launch
 
 struct RuArgs {
-    const float* x[kPtrSlots];      // x[s*np + q]: q-th term of segment s (np terms per segment)
+    const float* x[kPtrSlots];      // x[x_begin[s] + q]: q-th term of segment s
     int64_t lo[kMaxSegs];           // segment s covers flat elements [lo[s], hi[s])
     int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
+    int16_t x_begin[kMaxSegs];
+    uint8_t n_terms[kMaxSegs];      // terms of segment s (read by per-segment launches only)
+    uint8_t seg_update[kMaxSegs];   // does segment s apply the update? (per-segment launches only)
     int32_t n_segs;
     int32_t reverse;                // walk the launch's tiles from the last to the first
     int32_t xcd_run;                // consecutive tiles per die (see mc_tiles.h); <= 1: plain
-    float* g;                       // may be null when UPDATE
-    float* w;                       // unused when !UPDATE
+    float* g;                       // may be null when every segment updates
+    float* w;                       // unused when no segment updates
     float* v;
     mc::UpdateParams up;
 };
 
 typedef float native_f4 __attribute__((ext_vector_type(4)));
 
-template <bool NT>
-__device__ __forceinline__ float4 load4(const float* p) {
-    if (NT) {
-        const native_f4 r = __builtin_nontemporal_load(reinterpret_cast<const native_f4*>(p));
-        return make_float4(r.x, r.y, r.z, r.w);
-    }
-    return *reinterpret_cast<const float4*>(p);
+// Contributions and the reduced gradient are touched once per step: streaming (non-temporal)
+// accesses, so that they do not displace weights and momentum from the caches.
+__device__ __forceinline__ float4 load_stream(const float* p) {
+    const native_f4 r = __builtin_nontemporal_load(reinterpret_cast<const native_f4*>(p));
+    return make_float4(r.x, r.y, r.z, r.w);
 }
 
-template <bool NT>
-__device__ __forceinline__ void store4(float* p, const float4& q) {
-    if (NT) {
-        const native_f4 val = {q.x, q.y, q.z, q.w};
-        __builtin_nontemporal_store(val, reinterpret_cast<native_f4*>(p));
-    } else {
-        *reinterpret_cast<float4*>(p) = q;
-    }
+__device__ __forceinline__ void store_stream(float* p, const float4& q) {
+    const native_f4 val = {q.x, q.y, q.z, q.w};
+    __builtin_nontemporal_store(val, reinterpret_cast<native_f4*>(p));
 }
 
-// P > 0: compile-time number of terms; P == 0: run-time count in `Prt` (up to MC_MAX_P).
-// UPDATE: the SGD step follows the sum (the rank holds the complete sum of these colours);
-// otherwise only the sum is written to g and w, v are never touched.
-// NT: streaming (non-temporal) loads of the contributions and store of g.
-template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool NT>
-__global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Prt) {
-    static_assert(HAS_G || UPDATE, "a launch must produce something");
-    constexpr bool NT_IN = NT, NT_G = NT;
+// What a launch does with the sum.
+enum : int {
+    kSumOnly = 0,      // write it to g (colours of which the rank is a leaf or inner node)
+    kUpdateAndG = 1,   // write it to g and apply the SGD step
+    kUpdateOnly = 2,   // apply the SGD step, g is not wanted
+    kPerSegment = 3    // each segment has its own number of terms and its own update flag
+};
+
+// One tile of one segment.  P > 0: compile-time number of terms; P == 0: run-time count `np`
+// (up to MC_MAX_P).  UPDATE: the SGD step follows the sum; otherwise only the sum is written to g
+// and w, v are never touched.  SS: weights and momentum are streamed instead of kept resident.
+template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
+__device__ __forceinline__ void ru_tile(const float* const* xs, int np, int64_t base, int64_t hi, float* g,
+                                        float* w, float* v, const mc::Hyper& hp) {
+    static_assert(HAS_G || UPDATE, "a tile must produce something");
     constexpr int64_t kTile = int64_t(THREADS) * 4 * U;
-    const int np = P > 0 ? P : Prt;
-    const mc::Hyper hp = mc::resolve(a.up);
-
-    // blockIdx -> (segment, tile); a handful of scalar compares.
-    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
-    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
-    int s = 0;
-    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
-    const int64_t lo = a.lo[s];
-    const int64_t hi = a.hi[s];
-    const int64_t base = lo + int64_t(blk - a.first_block[s]) * kTile;
-    const float* const* xs = a.x + s * np;
-
     if (base + kTile <= hi) {
         // Full tile: issue every load of the tile before the first add.
         float4 acc[U], wv[U], vv[U];
@@ -96,12 +85,12 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
 #pragma unroll
             for (int q = 0; q < P; ++q)
 #pragma unroll
-                for (int u = 0; u < U; ++u) t[q][u] = load4<NT_IN>(xs[q] + idx[u]);
+                for (int u = 0; u < U; ++u) t[q][u] = load_stream(xs[q] + idx[u]);
             if (UPDATE) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    wv[u] = *reinterpret_cast<const float4*>(a.w + idx[u]);
-                    vv[u] = *reinterpret_cast<const float4*>(a.v + idx[u]);
+                    wv[u] = mc::load_state<SS>(w + idx[u]);
+                    vv[u] = mc::load_state<SS>(v + idx[u]);
                 }
             }
 #pragma unroll
@@ -119,10 +108,10 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (UPDATE) {
-                    wv[u] = *reinterpret_cast<const float4*>(a.w + idx[u]);
-                    vv[u] = *reinterpret_cast<const float4*>(a.v + idx[u]);
+                    wv[u] = mc::load_state<SS>(w + idx[u]);
+                    vv[u] = mc::load_state<SS>(v + idx[u]);
                 }
-                acc[u] = load4<NT_IN>(xs[0] + idx[u]);
+                acc[u] = load_stream(xs[0] + idx[u]);
             }
             // Four terms' loads are issued before their adds (more bytes in flight); the adds
             // still run strictly left to right.
@@ -132,7 +121,7 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
-                    for (int u = 0; u < U; ++u) t[r][u] = load4<NT_IN>(xs[q + r] + idx[u]);
+                    for (int u = 0; u < U; ++u) t[r][u] = load_stream(xs[q + r] + idx[u]);
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -147,7 +136,7 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
                 const float* xq = xs[q];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const float4 t = load4<NT_IN>(xq + idx[u]);
+                    const float4 t = load_stream(xq + idx[u]);
                     acc[u].x = acc[u].x + t.x;
                     acc[u].y = acc[u].y + t.y;
                     acc[u].z = acc[u].z + t.z;
@@ -157,99 +146,152 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (HAS_G) store4<NT_G>(a.g + idx[u], acc[u]);
+            if (HAS_G) store_stream(g + idx[u], acc[u]);
             if (UPDATE) {
                 mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
                 mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
                 mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
                 mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-                mc::store_state(a.w + idx[u], wv[u], hp.state_store_sc1);
-                mc::store_state(a.v + idx[u], vv[u], hp.state_store_sc1);
+                mc::store_state<SS>(w + idx[u], wv[u], hp.state_store_sc1);
+                mc::store_state<SS>(v + idx[u], vv[u], hp.state_store_sc1);
             }
         }
         return;
     }
 
     // Last, partial tile of the segment: whole vectors while they fit, then single elements.
-    // (lo is a multiple of 256 elements, so base is 16-byte aligned; hi need not be.)
+    // (Segments start on multiples of 256 elements, so base is 16-byte aligned; hi need not be.)
     for (int u = 0; u < U; ++u) {
         const int64_t i = base + (int64_t(u) * THREADS + threadIdx.x) * 4;
         if (i >= hi) break;
         if (i + 4 <= hi) {
-            float4 acc = load4<NT_IN>(xs[0] + i);
+            float4 acc = load_stream(xs[0] + i);
             for (int q = 1; q < np; ++q) {
-                const float4 t = load4<NT_IN>(xs[q] + i);
+                const float4 t = load_stream(xs[q] + i);
                 acc.x = acc.x + t.x;
                 acc.y = acc.y + t.y;
                 acc.z = acc.z + t.z;
                 acc.w = acc.w + t.w;
             }
-            if (HAS_G) *reinterpret_cast<float4*>(a.g + i) = acc;
+            if (HAS_G) *reinterpret_cast<float4*>(g + i) = acc;
             if (UPDATE) {
-                float4 wq = *reinterpret_cast<const float4*>(a.w + i);
-                float4 vq = *reinterpret_cast<const float4*>(a.v + i);
+                float4 wq = *reinterpret_cast<const float4*>(w + i);
+                float4 vq = *reinterpret_cast<const float4*>(v + i);
                 mc::sgd(acc.x, wq.x, vq.x, hp);
                 mc::sgd(acc.y, wq.y, vq.y, hp);
                 mc::sgd(acc.z, wq.z, vq.z, hp);
                 mc::sgd(acc.w, wq.w, vq.w, hp);
-                *reinterpret_cast<float4*>(a.w + i) = wq;
-                *reinterpret_cast<float4*>(a.v + i) = vq;
+                *reinterpret_cast<float4*>(w + i) = wq;
+                *reinterpret_cast<float4*>(v + i) = vq;
             }
         } else {
             for (int64_t e = i; e < hi; ++e) {
                 float acc = xs[0][e];
                 for (int q = 1; q < np; ++q) acc = acc + xs[q][e];
-                if (HAS_G) a.g[e] = acc;
+                if (HAS_G) g[e] = acc;
                 if (UPDATE) {
-                    float we = a.w[e], ve = a.v[e];
+                    float we = w[e], ve = v[e];
                     mc::sgd(acc, we, ve, hp);
-                    a.w[e] = we;
-                    a.v[e] = ve;
+                    w[e] = we;
+                    v[e] = ve;
                 }
             }
         }
     }
 }
 
-template <int P, int U>
-void launch_variant(bool update, bool nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    constexpr int T = kThreads;
-    const dim3 grid(blocks), block(T);
-#define MC_RU_LAUNCH(G, UPD, NT) \
-    hipLaunchKernelGGL((reduce_update_kernel<P, U, T, G, UPD, NT>), grid, block, 0, s, a, Prt)
-    if (!update) {
-        if (nt) MC_RU_LAUNCH(true, false, true); else MC_RU_LAUNCH(true, false, false);
-    } else if (a.g) {
-        if (nt) MC_RU_LAUNCH(true, true, true); else MC_RU_LAUNCH(true, true, false);
+// A per-segment launch picks the compile-time body of the segment's term count.
+template <int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
+__device__ __forceinline__ void ru_tile_any(const float* const* xs, int np, int64_t base, int64_t hi, float* g,
+                                            float* w, float* v, const mc::Hyper& hp) {
+    switch (np) {
+        case 1: ru_tile<1, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 2: ru_tile<2, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 3: ru_tile<3, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 4: ru_tile<4, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 5: ru_tile<5, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 6: ru_tile<6, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 7: ru_tile<7, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 8: ru_tile<8, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        default: ru_tile<0, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+    }
+}
+
+template <int P, int U, int THREADS, int MODE, bool SS>
+__global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Prt) {
+    constexpr int64_t kTile = int64_t(THREADS) * 4 * U;
+    const mc::Hyper hp = mc::resolve(a.up);
+
+    // blockIdx -> (segment, tile); a handful of scalar compares.
+    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
+    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
+    int s = 0;
+    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
+    const int64_t hi = a.hi[s];
+    const int64_t base = a.lo[s] + int64_t(blk - a.first_block[s]) * kTile;
+    const float* const* xs = a.x + a.x_begin[s];
+
+    if (MODE == kPerSegment) {
+        const int np = a.n_terms[s];
+        if (a.seg_update[s]) {
+            if (a.g)
+                ru_tile_any<U, THREADS, true, true, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
+            else
+                ru_tile_any<U, THREADS, false, true, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
+        } else {
+            ru_tile_any<U, THREADS, true, false, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
+        }
     } else {
-        if (nt) MC_RU_LAUNCH(false, true, true); else MC_RU_LAUNCH(false, true, false);
+        const int np = P > 0 ? P : Prt;
+        ru_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
+    }
+}
+
+template <int P, int U, int T>
+void launch_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
+    const dim3 grid(blocks), block(T);
+#define MC_RU_LAUNCH(MODE, SS) hipLaunchKernelGGL((reduce_update_kernel<P, U, T, MODE, SS>), grid, block, 0, s, a, Prt)
+    switch (mode) {
+        case kSumOnly: MC_RU_LAUNCH(kSumOnly, false); break;   // state is not touched: one policy
+        case kUpdateAndG: if (ss) MC_RU_LAUNCH(kUpdateAndG, true); else MC_RU_LAUNCH(kUpdateAndG, false); break;
+        default: if (ss) MC_RU_LAUNCH(kUpdateOnly, true); else MC_RU_LAUNCH(kUpdateOnly, false); break;
     }
 #undef MC_RU_LAUNCH
 }
 
 template <int P>
-void launch_unroll(int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
-    if (unroll == 1)
-        launch_variant<P, 1>(update, nt, blocks, s, a, Prt);
+void launch_shape(mc::Shape shape, int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
+    if (shape.threads == 64)
+        launch_mode<P, 1, 64>(mode, ss, blocks, s, a, Prt);
     else
-        launch_variant<P, 2>(update, nt, blocks, s, a, Prt);
+        launch_mode<P, 2, 256>(mode, ss, blocks, s, a, Prt);
 }
 
-void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_t s, const RuArgs& a) {
+// A launch whose segments all add P terms and agree on updating.
+void launch(int P, mc::Shape shape, int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a) {
     switch (P) {
-        case 1: launch_unroll<1>(unroll, update, nt, blocks, s, a, P); break;
-        case 2: launch_unroll<2>(unroll, update, nt, blocks, s, a, P); break;
-        case 3: launch_unroll<3>(unroll, update, nt, blocks, s, a, P); break;
-        case 4: launch_unroll<4>(unroll, update, nt, blocks, s, a, P); break;
-        case 5: launch_unroll<5>(unroll, update, nt, blocks, s, a, P); break;
-        case 6: launch_unroll<6>(unroll, update, nt, blocks, s, a, P); break;
-        case 7: launch_unroll<7>(unroll, update, nt, blocks, s, a, P); break;
-        case 8: launch_unroll<8>(unroll, update, nt, blocks, s, a, P); break;
-        default: launch_unroll<0>(unroll, update, nt, blocks, s, a, P); break;
+        case 1: launch_shape<1>(shape, mode, ss, blocks, s, a, P); break;
+        case 2: launch_shape<2>(shape, mode, ss, blocks, s, a, P); break;
+        case 3: launch_shape<3>(shape, mode, ss, blocks, s, a, P); break;
+        case 4: launch_shape<4>(shape, mode, ss, blocks, s, a, P); break;
+        case 5: launch_shape<5>(shape, mode, ss, blocks, s, a, P); break;
+        case 6: launch_shape<6>(shape, mode, ss, blocks, s, a, P); break;
+        case 7: launch_shape<7>(shape, mode, ss, blocks, s, a, P); break;
+        case 8: launch_shape<8>(shape, mode, ss, blocks, s, a, P); break;
+        default: launch_shape<0>(shape, mode, ss, blocks, s, a, P); break;
     }
 }
 
-// Shared by both entry points.  n_terms / do_update are null for the uniform call (every
+// A launch whose segments differ in term count or update flag (always 64 threads x 1 vector).
+void launch_per_segment(bool ss, unsigned blocks, hipStream_t s, const RuArgs& a) {
+    const dim3 grid(blocks), block(64);
+    if (ss)
+        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, true>), grid, block, 0, s, a, 0);
+    else
+        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, false>), grid, block, 0, s, a, 0);
+}
+
+// Shared by every entry point.  n_terms / do_update are null for the uniform call (every
 // colour adds all P terms and updates).
 //
 // [r_lo, r_hi) restricts the call to a sub-range of the payload (a packet): every colour is
@@ -257,9 +299,9 @@ void launch(int P, int unroll, bool update, bool nt, unsigned blocks, hipStream_
 // N), so every segment still starts on a 16-byte boundary.
 int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
              const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
-             void* momentum, const mc::UpdateParams& up, int64_t r_lo, int64_t r_hi, void* stream) {
+             void* momentum, const mc::UpdatePlan& plan, int64_t r_lo, int64_t r_hi, void* stream) {
     if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
-    if (up.hyper && !mc::aligned(up.hyper, 4)) return MC_ERR_ALIGN;
+    if (plan.up.hyper && !mc::aligned(plan.up.hyper, 4)) return MC_ERR_ALIGN;
     if (r_lo < 0 || r_hi < r_lo || r_hi > L->N) return MC_ERR_INVALID_ARG;
     if (r_lo % MC_COLOUR_ALIGN_ELEMS != 0) return MC_ERR_INVALID_ARG;
     if (r_hi % MC_COLOUR_ALIGN_ELEMS != 0 && r_hi != L->N) return MC_ERR_INVALID_ARG;
@@ -274,103 +316,113 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
             }
         }
     }
-    // What colour c contributes to this call: its range cut to [r_lo, r_hi).
+    // What colour c contributes to this call: its range cut to [r_lo, r_hi), its term count and
+    // whether it updates.
     auto seg_lo = [&](int32_t c) { return std::max(L->bounds[c], r_lo); };
     auto seg_hi = [&](int32_t c) { return std::max(seg_lo(c), std::min(L->bounds[c + 1], r_hi)); };
-    bool any_update = false, any_sum_only = false;
+    auto terms = [&](int32_t c) { return n_terms ? n_terms[c] : P; };
+    auto updates = [&](int32_t c) { return do_update ? do_update[c] != 0 : true; };
+    auto active = [&](int32_t c) { return terms(c) > 0 && seg_hi(c) > seg_lo(c); };
+    bool any_update = false, any_sum_only = false, uniform = true;
+    int32_t first_active = -1;
     for (int32_t c = 0; c < L->k; ++c) {
         if (n_terms && (n_terms[c] < 0 || n_terms[c] > P)) return MC_ERR_INVALID_ARG;
-        if ((n_terms && n_terms[c] == 0) || seg_hi(c) == seg_lo(c)) continue;
-        if (!do_update || do_update[c]) any_update = true; else any_sum_only = true;
+        if (!active(c)) continue;
+        if (updates(c)) any_update = true; else any_sum_only = true;
+        if (first_active < 0) first_active = c;
+        else if (terms(c) != terms(first_active) || updates(c) != updates(first_active)) uniform = false;
     }
-    if (!any_update && !any_sum_only) return MC_OK;  // nothing in range
+    if (first_active < 0) return MC_OK;  // nothing in range
     if (any_update && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
     if (any_sum_only && !grad_out) return MC_ERR_INVALID_ARG;
     for (int32_t p = 0; p < P; ++p)
         if (!contrib[p]) return MC_ERR_INVALID_ARG;
 
-    // Alignment and overlap over the whole list {contrib[0..P), weights, momentum, grad_out}.
-    const void* bufs[MC_MAX_P + 3];
-    int nb = 0;
-    for (int32_t p = 0; p < P; ++p) bufs[nb++] = contrib[p];
-    if (weights) bufs[nb++] = weights;
-    if (momentum) bufs[nb++] = momentum;
-    if (grad_out) bufs[nb++] = grad_out;
-    for (int i = 0; i < nb; ++i)
-        if (!mc::aligned(bufs[i], 16)) return MC_ERR_ALIGN;
+    // Alignment of every buffer; nothing that is written (weights, momentum, grad_out) may overlap
+    // anything else of the call.  Contributions are only read, so the same buffer may appear twice.
+    const void* written[3];
+    int nw = 0;
+    if (weights) written[nw++] = weights;
+    if (momentum) written[nw++] = momentum;
+    if (grad_out) written[nw++] = grad_out;
+    for (int32_t p = 0; p < P; ++p)
+        if (!mc::aligned(contrib[p], 16)) return MC_ERR_ALIGN;
+    for (int i = 0; i < nw; ++i)
+        if (!mc::aligned(written[i], 16)) return MC_ERR_ALIGN;
     const uint64_t bytes = uint64_t(L->N) * 4;
-    for (int i = 0; i < nb; ++i)
-        for (int j = i + 1; j < nb; ++j)
-            if (mc::overlaps(bufs[i], bytes, bufs[j], bytes)) return MC_ERR_OVERLAP;
+    for (int i = 0; i < nw; ++i) {
+        for (int j = i + 1; j < nw; ++j)
+            if (mc::overlaps(written[i], bytes, written[j], bytes)) return MC_ERR_OVERLAP;
+        for (int32_t p = 0; p < P; ++p)
+            if (mc::overlaps(written[i], bytes, contrib[p], bytes)) return MC_ERR_OVERLAP;
+    }
 
-    const int unroll = mc::unroll_for(r_hi - r_lo);
-    const bool nt = mc::option(MC_OPT_RU_NONTEMPORAL) != 0;
-    const int64_t tile = int64_t(kThreads) * 4 * unroll;
+    const bool ss = any_update && mc::stream_state(L, plan.state_policy);
+    const int max_terms = [&] { int m = 0; for (int32_t c = 0; c < L->k; ++c) if (active(c)) m = std::max(m, terms(c)); return m; }();
+    // Launches that mix term counts or update flags use the one-wavefront shape.
+    const mc::Shape shape = uniform ? mc::shape_for(r_hi - r_lo, max_terms, ss) : mc::Shape{64, 1};
+    const int64_t tile = shape.tile();
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     RuArgs a;
-    // Only the plain whole-payload step alternates: packets and role calls come several to a step.
-    a.reverse = (!n_terms && r_lo == 0 && r_hi == L->N && mc::sweep_reversed(L)) ? 1 : 0;
+    // Only the plain whole-payload step alternates by itself: packets and role calls come several to a step.
+    const bool whole = !n_terms && r_lo == 0 && r_hi == L->N;
+    a.reverse = mc::sweep_reversed(L, whole ? plan.sweep : (plan.sweep == MC_SWEEP_AUTO ? MC_SWEEP_FORWARD : plan.sweep), ss) ? 1 : 0;
     a.xcd_run = mc::option(MC_OPT_XCD_RUN);
     a.g = static_cast<float*>(grad_out);
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);
-    a.up = up;
+    a.up = plan.up;
 
-    // Colours that add the same number of terms and agree on updating share launches (a rank is
-    // inner node or root for at most one colour, so there are at most two such classes in
-    // practice; the uniform call has one).  `done` marks colours already launched.
-    std::vector<uint8_t> done(size_t(L->k), 0);
-    for (int32_t c0 = 0; c0 < L->k; ++c0) {
-        if (done[c0]) continue;
-        const int32_t cnt = n_terms ? n_terms[c0] : P;
-        const bool upd = do_update ? do_update[c0] != 0 : true;
-        if (cnt == 0 || seg_hi(c0) == seg_lo(c0)) {
-            done[c0] = 1;
-            continue;
-        }
-        const int segs_per_launch = std::min(kMaxSegs, kPtrSlots / cnt);
-        int32_t c = c0;
-        while (c < L->k) {
-            int ns = 0;
-            int64_t blocks = 0;
-            a.first_block[0] = 0;
-            for (; c < L->k && ns < segs_per_launch; ++c) {
-                if (done[c]) continue;
-                const int64_t lo = seg_lo(c), hi = seg_hi(c);
-                const int32_t cc = n_terms ? n_terms[c] : P;
-                const bool cu = do_update ? do_update[c] != 0 : true;
-                if (cc == 0 || hi == lo) {
-                    done[c] = 1;
-                    continue;
-                }
-                if (cc != cnt || cu != upd) continue;  // another class: a later pass takes it
-                const int64_t nblk = (hi - lo + tile - 1) / tile;
-                if (blocks + nblk > 0x7fffffff) {
-                    if (ns == 0) return MC_ERR_INVALID_ARG;
-                    break;
-                }
-                a.lo[ns] = lo;
-                a.hi[ns] = hi;
-                for (int32_t q = 0; q < cnt; ++q) {
-                    const int32_t src = order ? order[size_t(c) * P + q] : q;
-                    a.x[ns * cnt + q] = static_cast<const float*>(contrib[src]);
-                }
-                blocks += nblk;
-                a.first_block[ns + 1] = int32_t(blocks);
-                done[c] = 1;
-                ++ns;
+    // Colours are taken in index order, as many per launch as the segment and pointer slots hold:
+    // one launch for any realistic call (a rank is inner node or root of at most one colour, so a
+    // role-dependent step has two kinds of segments and they share the launch).
+    int32_t c = 0;
+    while (c < L->k) {
+        int ns = 0, slots = 0;
+        int64_t blocks = 0;
+        a.first_block[0] = 0;
+        for (; c < L->k && ns < kMaxSegs; ++c) {
+            if (!active(c)) continue;
+            const int32_t cnt = terms(c);
+            if (slots + cnt > kPtrSlots) break;
+            const int64_t lo = seg_lo(c), hi = seg_hi(c);
+            const int64_t nblk = (hi - lo + tile - 1) / tile;
+            if (blocks + nblk > 0x7fffffff) {
+                if (ns == 0) return MC_ERR_INVALID_ARG;
+                break;
             }
-            if (ns == 0) break;
-            for (int i = ns * cnt; i < kPtrSlots; ++i) a.x[i] = nullptr;
-            for (int i = ns; i < kMaxSegs; ++i) {
-                a.lo[i] = a.hi[i] = 0;
-                a.first_block[i + 1] = a.first_block[ns];
+            a.lo[ns] = lo;
+            a.hi[ns] = hi;
+            a.x_begin[ns] = int16_t(slots);
+            a.n_terms[ns] = uint8_t(cnt);
+            a.seg_update[ns] = updates(c) ? 1 : 0;
+            for (int32_t q = 0; q < cnt; ++q) {
+                const int32_t src = order ? order[size_t(c) * P + q] : q;
+                a.x[slots + q] = static_cast<const float*>(contrib[src]);
             }
-            a.n_segs = ns;
-            launch(cnt, unroll, upd, nt, unsigned(blocks), s, a);
-            MC_HIP_TRY(hipGetLastError());
+            slots += cnt;
+            blocks += nblk;
+            a.first_block[ns + 1] = int32_t(blocks);
+            ++ns;
         }
+        if (ns == 0) break;
+        for (int i = slots; i < kPtrSlots; ++i) a.x[i] = nullptr;
+        for (int i = ns; i < kMaxSegs; ++i) {
+            a.lo[i] = a.hi[i] = 0;
+            a.x_begin[i] = 0;
+            a.n_terms[i] = 0;
+            a.seg_update[i] = 0;
+            a.first_block[i + 1] = a.first_block[ns];
+        }
+        a.n_segs = ns;
+        if (uniform) {
+            const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
+            launch(terms(first_active), shape, mode, ss, unsigned(blocks), s, a);
+        } else {
+            launch_per_segment(ss, unsigned(blocks), s, a);
+        }
+        MC_HIP_TRY(hipGetLastError());
     }
     return MC_OK;
 }
@@ -378,38 +430,44 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
 // No C++ exception may cross the C boundary.
 int run(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
         const int32_t* n_terms, const uint8_t* do_update, void* grad_out, void* weights,
-        void* momentum, const mc::UpdateParams& up, int64_t r_lo, int64_t r_hi, void* stream) {
+        void* momentum, const mc::UpdatePlan& plan, int64_t r_lo, int64_t r_hi, void* stream) {
     try {
-        return run_impl(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up,
+        return run_impl(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, plan,
                         r_lo, r_hi, stream);
     } catch (const std::bad_alloc&) {
         return MC_ERR_ALLOC;
     }
 }
 
-mc::UpdateParams immediate(float lr, float mu, float wd) {
-    mc::UpdateParams up;
-    up.lr = lr;
-    up.mu = mu;
-    up.wd = wd;
-    up.hyper = nullptr;
-    up.nesterov = 0;
-    up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
-    return up;
+mc::UpdatePlan immediate(float lr, float mu, float wd) {
+    mc::UpdatePlan plan;
+    plan.up.lr = lr;
+    plan.up.mu = mu;
+    plan.up.wd = wd;
+    plan.up.hyper = nullptr;
+    plan.up.nesterov = 0;
+    plan.up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
+    plan.state_policy = MC_STATE_DEFAULT;
+    plan.sweep = MC_SWEEP_AUTO;
+    return plan;
 }
 
 }  // namespace
 
 namespace mc {
 
-int update_params(const mc_update_spec* spec, UpdateParams* out) {
+int update_plan(const mc_update_spec* spec, UpdatePlan* out) {
     if (!spec || (spec->nesterov != 0 && spec->nesterov != 1)) return MC_ERR_INVALID_ARG;
-    out->lr = spec->lr;
-    out->mu = spec->mu;
-    out->wd = spec->wd;
-    out->hyper = spec->hyper_dev;
-    out->nesterov = spec->nesterov;
-    out->state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
+    if (spec->state_policy < MC_STATE_DEFAULT || spec->state_policy > MC_STATE_STREAMING) return MC_ERR_INVALID_ARG;
+    if (spec->sweep < MC_SWEEP_AUTO || spec->sweep > MC_SWEEP_BACKWARD) return MC_ERR_INVALID_ARG;
+    out->up.lr = spec->lr;
+    out->up.mu = spec->mu;
+    out->up.wd = spec->wd;
+    out->up.hyper = spec->hyper_dev;
+    out->up.nesterov = spec->nesterov;
+    out->up.state_store_sc1 = mc::option(MC_OPT_STATE_STORE_SC1);
+    out->state_policy = spec->state_policy;
+    out->sweep = spec->sweep;
     return MC_OK;
 }
 
@@ -448,10 +506,10 @@ int mc_reduce_update_ex(const mc_layout* L, const void* const* contrib, int32_t 
                         void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
                         int64_t elem_begin, int64_t elem_end, void* stream) {
     if (!L) return MC_ERR_INVALID_ARG;
-    mc::UpdateParams up;
-    const int rc = mc::update_params(spec, &up);
+    mc::UpdatePlan plan;
+    const int rc = mc::update_plan(spec, &plan);
     if (rc != MC_OK) return rc;
-    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, up,
+    return run(L, contrib, P, order, n_terms, do_update, grad_out, weights, momentum, plan,
                elem_begin, elem_end < 0 ? L->N : elem_end, stream);
 }
 

@@ -25,12 +25,16 @@ MAX_P = 32
 NOALLOC_MAX_TENSORS = 256
 NOALLOC_MAX_ELEMS = 1 << 28
 COLOUR_ALIGN_ELEMS = 256
-OPT_RU_UNROLL = 1
-OPT_RU_NONTEMPORAL = 2
+OPT_RU_SHAPE = 1
+OPT_STATE_POLICY = 2
 OPT_PACK_NONTEMPORAL = 3
 OPT_STATE_STORE_SC1 = 4
 OPT_ALTERNATE_SWEEP = 5
 OPT_XCD_RUN = 6
+OPT_XCD_RUN_PACK = 7
+OPT_XCD_RUN_UNPACK = 8
+STATE_DEFAULT, STATE_RESIDENT, STATE_STREAMING = 0, 1, 2
+SWEEP_AUTO, SWEEP_FORWARD, SWEEP_BACKWARD = 0, 1, 2
 ROLE_LEAF, ROLE_INNER, ROLE_ROOT = 0, 1, 2
 
 _i64p = ctypes.POINTER(ctypes.c_int64)
@@ -365,14 +369,16 @@ def fused_step(layout: Layout, contrib_sets, order, grad_out_ptr: Optional[int],
 
 
 class UpdateSpec(ctypes.Structure):
-    """mc_update_spec: immediate {lr, mu, wd} or a device pointer to them, and the Nesterov flag."""
+    """mc_update_spec: immediate {lr, mu, wd} or a device pointer to them, the Nesterov flag, and
+    the two choices that change how memory is walked but never a result (STATE_*, SWEEP_*)."""
     _fields_ = [("lr", ctypes.c_float), ("mu", ctypes.c_float), ("wd", ctypes.c_float),
-                ("hyper_dev", ctypes.c_void_p), ("nesterov", ctypes.c_int32)]
+                ("hyper_dev", ctypes.c_void_p), ("nesterov", ctypes.c_int32),
+                ("state_policy", ctypes.c_int32), ("sweep", ctypes.c_int32)]
 
 
 def update_spec(lr: float = 0.0, mu: float = 0.0, wd: float = 0.0, hyper_dev_ptr: Optional[int] = None,
-                nesterov: int = 0) -> UpdateSpec:
-    return UpdateSpec(lr, mu, wd, hyper_dev_ptr, int(nesterov))
+                nesterov: int = 0, state_policy: int = STATE_DEFAULT, sweep: int = SWEEP_AUTO) -> UpdateSpec:
+    return UpdateSpec(lr, mu, wd, hyper_dev_ptr, int(nesterov), int(state_policy), int(sweep))
 
 
 def _order_ptr(order, k: int, P: int):

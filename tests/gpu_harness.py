@@ -168,7 +168,9 @@ class FusedStep:
         self.O = oracle.Layout(self.sizes, k)
 
     def run(self, contrib_tensors, w_tensors, v_tensors, lr, mu, wd, order=None, want_g=True,
-            misalign=None, misalign_w=None):
+            misalign=None, misalign_w=None, spec=None):
+        """spec: an mc.UpdateSpec carrying the same lr, mu, wd -> mc_fused_step_ex instead of
+        mc_fused_step (the oracle's answer is the same)."""
         L, O = self.L, self.O
         s = stream_handle()
         placed = [place_tensors(ts, misalign) for ts in contrib_tensors]
@@ -182,7 +184,10 @@ class FusedStep:
         g_ptr = gbuf[G:].data_ptr() if want_g else None
         arenas_before = [a.cpu().numpy().view(np.uint32).copy() if a is not None else None
                          for a in (w_arena, v_arena)]
-        mc.fused_step(L, sets, order, g_ptr if L.N else None, wset, vset, lr, mu, wd, s)
+        if spec is None:
+            mc.fused_step(L, sets, order, g_ptr if L.N else None, wset, vset, lr, mu, wd, s)
+        else:
+            mc.fused_step_ex(L, sets, order, g_ptr if L.N else None, wset, vset, spec, s)
         torch.cuda.synchronize()
         N = L.N
         gpu = dict(g=gbuf[G:G + N].cpu().numpy() if want_g else None,

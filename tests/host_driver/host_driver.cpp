@@ -85,7 +85,7 @@ int main() {
     REQUIRE(mc_lr_schedule(0.1f, 32, 256, 5.f, 30.f, 31.f, &lr) == MC_OK && lr > 0.31f && lr < 0.33f);
     REQUIRE(mc_lr_schedule(0.1f, 0, 256, 5.f, 30.f, 31.f, &lr) == MC_ERR_INVALID_ARG);
     int v = 0;
-    REQUIRE(mc_get_option(MC_OPT_RU_UNROLL, &v) == MC_OK && mc_set_option(MC_OPT_RU_UNROLL, v) == MC_OK);
+    REQUIRE(mc_get_option(MC_OPT_RU_SHAPE, &v) == MC_OK && mc_set_option(MC_OPT_RU_SHAPE, v) == MC_OK);
     REQUIRE(mc_set_option(12345, 1) == MC_ERR_INVALID_ARG);
     for (int code = -7; code <= 1; ++code) REQUIRE(mc_strerror(code) != nullptr);
     std::printf("host_driver: ok\n");

@@ -140,7 +140,6 @@ def test_reduce_update_rejects_before_launch():
     assert _code(ru, L, x, None, g + 8, w, v, .1, .9, 0.) == mc.ERR_ALIGN
     assert _code(ru, L, x, None, g, w + 4, v, .1, .9, 0.) == mc.ERR_ALIGN
     assert _code(ru, L, x, None, g, w, v + 12, .1, .9, 0.) == mc.ERR_ALIGN
-    assert _code(ru, L, [x[0], x[0]], None, g, w, v, .1, .9, 0.) == mc.ERR_OVERLAP
     assert _code(ru, L, x, None, x[2], w, v, .1, .9, 0.) == mc.ERR_OVERLAP
     assert _code(ru, L, x, None, g, w, w, .1, .9, 0.) == mc.ERR_OVERLAP
     assert _code(ru, L, x, None, g, w, w + 4 * N - 16, .1, .9, 0.) == mc.ERR_OVERLAP     # last vector
@@ -175,13 +174,15 @@ def test_empty_payload_is_a_no_op():
 
 
 def test_options():
-    assert mc.get_option(mc.OPT_RU_UNROLL) in (0, 1, 2)
-    for opt, good, bad in ((mc.OPT_RU_UNROLL, (0, 1, 2), (-1, 3, 4)),
-                           (mc.OPT_RU_NONTEMPORAL, (0, 1), (-1, 2)),
+    assert mc.get_option(mc.OPT_RU_SHAPE) in (0, 1, 2)
+    for opt, good, bad in ((mc.OPT_RU_SHAPE, (0, 1, 2), (-1, 3, 4)),
+                           (mc.OPT_STATE_POLICY, (0, 1, 2), (-1, 3)),
                            (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4)),
                            (mc.OPT_STATE_STORE_SC1, (0, 1), (-1, 2)),
                            (mc.OPT_ALTERNATE_SWEEP, (0, 1), (-1, 2)),
-                           (mc.OPT_XCD_RUN, (0, 1, 8, 64), (-1, 65))):
+                           (mc.OPT_XCD_RUN, (0, 1, 8, 64), (-1, 65)),
+                           (mc.OPT_XCD_RUN_PACK, (-1, 0, 16, 64), (-2, 65)),
+                           (mc.OPT_XCD_RUN_UNPACK, (-1, 0, 16, 64), (-2, 65))):
         keep = mc.get_option(opt)
         for g in good:
             mc.set_option(opt, g)

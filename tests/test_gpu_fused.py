@@ -16,7 +16,7 @@ import gpu_harness as gh  # noqa: E402
 
 @pytest.fixture(autouse=True)
 def _restore_options():
-    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL, mc.OPT_STATE_STORE_SC1)}
+    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_SHAPE, mc.OPT_STATE_POLICY, mc.OPT_STATE_STORE_SC1)}
     yield
     for o, v in keep.items():
         mc.set_option(o, v)
@@ -53,8 +53,8 @@ ALIGNED_SIZES = [64, 64, 36864, 64, 16384, 4096, 256, 256, 147456, 512, 8, 65536
 @pytest.mark.parametrize("misalign", [None, [0, 0, 1, 0, 0, 2]])
 def test_cnn_like_layout(unroll, nt, misalign):
     mc.set_option(mc.OPT_STATE_STORE_SC1, (unroll + nt) % 2)
-    mc.set_option(mc.OPT_RU_UNROLL, unroll)
-    mc.set_option(mc.OPT_RU_NONTEMPORAL, nt)
+    mc.set_option(mc.OPT_RU_SHAPE, unroll)
+    mc.set_option(mc.OPT_STATE_POLICY, 1 + nt)
     k, P = 3, 4
     st = gh.FusedStep(ALIGNED_SIZES, k)
     xs, w, v = _inputs(ALIGNED_SIZES, P, heavy=True)

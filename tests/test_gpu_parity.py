@@ -17,7 +17,7 @@ import gpu_harness as gh  # noqa: E402
 
 @pytest.fixture(autouse=True)
 def _restore_options():
-    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_UNROLL, mc.OPT_RU_NONTEMPORAL, mc.OPT_PACK_NONTEMPORAL, mc.OPT_STATE_STORE_SC1)}
+    keep = {o: mc.get_option(o) for o in (mc.OPT_RU_SHAPE, mc.OPT_STATE_POLICY, mc.OPT_PACK_NONTEMPORAL, mc.OPT_STATE_STORE_SC1)}
     yield
     for o, v in keep.items():
         mc.set_option(o, v)
@@ -56,9 +56,9 @@ def test_tiny_config(order_kind, misalign):
 @pytest.mark.parametrize("pack_nt", [0, 1, 2, 3])
 def test_launch_shapes_do_not_change_bits(unroll, nt, pack_nt):
     mc.set_option(mc.OPT_STATE_STORE_SC1, (unroll + nt + pack_nt) % 2)
-    mc.set_option(mc.OPT_RU_UNROLL, unroll)
+    mc.set_option(mc.OPT_RU_SHAPE, unroll)
     mc.set_option(mc.OPT_PACK_NONTEMPORAL, pack_nt)
-    mc.set_option(mc.OPT_RU_NONTEMPORAL, nt)
+    mc.set_option(mc.OPT_STATE_POLICY, 1 + nt)
     sizes = [30000, 1, 4097, 12345, 70001]      # several tiles of every shape + ragged tail
     st = gh.Step(sizes, 3)
     xs, w, v = _inputs(sizes, 5, v_zero=False)
@@ -77,6 +77,26 @@ def test_every_contribution_count(P):
     for order in (None, wl.random_order(k, P, seed=P)):
         gpu, ref = st.run(xs, w, v, 0.05, 0.8, 1e-3, order=order, unpack_outputs=False)
         st.check(gpu, ref, 0.05, 0.8, 1e-3, f"P={P}")
+
+
+def test_the_same_contribution_twice():
+    """Contributions are only read, so one buffer may be given more than once (x + x + y)."""
+    sizes = [5000, 3, 2049, 8191]
+    k = 2
+    L = mc.Layout(sizes, k)
+    O = oracle.Layout(sizes, k)
+    xs, w, v = _inputs(sizes, 2, v_zero=False)
+    xf = [oracle.pack(O, t) for t in xs]
+    wf, vf = oracle.pack(O, w), oracle.pack(O, v)
+    xd = [gh.to_dev(x) for x in xf]
+    wd_, vd, gd = gh.to_dev(wf), gh.to_dev(vf), gh.dev_empty(L.N)
+    mc.reduce_update(L, [xd[0].data_ptr(), xd[0].data_ptr(), xd[1].data_ptr()], None, gd.data_ptr(),
+                     wd_.data_ptr(), vd.data_ptr(), 0.1, 0.9, 1e-4, gh.stream_handle())
+    torch.cuda.synchronize()
+    g = oracle.reduce_update(O, [xf[0], xf[0], xf[1]], wf, vf, 0.1, 0.9, 1e-4)
+    gh.assert_bits(gd[:L.N].cpu().numpy(), g, "g")
+    gh.assert_bits(wd_.cpu().numpy(), wf, "w")
+    gh.assert_bits(vd.cpu().numpy(), vf, "v")
 
 
 @pytest.mark.parametrize("sizes,k", [
@@ -371,11 +391,12 @@ def test_pack_and_unpack_through_tensor_sets_with_thousands_of_tensors():
 
 @pytest.mark.parametrize("alternate", [0, 1])
 def test_sweep_direction_does_not_change_bits(alternate):
-    """Successive whole-payload calls on one layout walk the payload in opposite directions
-    (a cache-reuse measure); the same step repeated from the same state must give the same bits
-    whichever direction it happens to get, in both forms of the step."""
-    keep = mc.get_option(mc.OPT_ALTERNATE_SWEEP)
+    """Successive whole-payload calls with resident state larger than the memory-side cache walk the
+    payload in opposite directions (a cache-reuse measure); the same step repeated from the same
+    state must give the same bits whichever direction it happens to get, in both forms of the step."""
+    keep = {o: mc.get_option(o) for o in (mc.OPT_ALTERNATE_SWEEP, mc.OPT_STATE_POLICY)}
     mc.set_option(mc.OPT_ALTERNATE_SWEEP, alternate)
+    mc.set_option(mc.OPT_STATE_POLICY, mc.STATE_RESIDENT)
     try:
         # above 32 Mi elements (256 MB of weights + momentum) the calls alternate when enabled
         sizes = [30000, 12, 4099, 70001] if alternate == 0 else [20_000_000, 12, 4099, 14_000_001]
@@ -389,7 +410,45 @@ def test_sweep_direction_does_not_change_bits(alternate):
             gpu, ref = fs.run(xs, w, v, 0.1, 0.9, 1e-4, order=order, misalign=[0])
             fs.check(gpu, ref, f"fused rep {rep}")
     finally:
-        mc.set_option(mc.OPT_ALTERNATE_SWEEP, keep)
+        for o, val in keep.items():
+            mc.set_option(o, val)
+
+
+@pytest.mark.parametrize("policy", [mc.STATE_DEFAULT, mc.STATE_RESIDENT, mc.STATE_STREAMING])
+@pytest.mark.parametrize("sweep", [mc.SWEEP_AUTO, mc.SWEEP_FORWARD, mc.SWEEP_BACKWARD])
+@pytest.mark.parametrize("shape", [1, 2])
+def test_state_policy_and_sweep_do_not_change_bits(policy, sweep, shape):
+    """The spec's state_policy and sweep fields choose cache treatment and walking direction only:
+    every combination must give the oracle's bits, several tiles per colour plus ragged ends."""
+    keep = mc.get_option(mc.OPT_RU_SHAPE)
+    mc.set_option(mc.OPT_RU_SHAPE, shape)
+    try:
+        sizes = [30000, 12, 4099, 70001, 5]
+        k, P = 3, 3
+        L = mc.Layout(sizes, k)
+        O = oracle.Layout(sizes, k)
+        xs, w, v = _inputs(sizes, P, v_zero=False)
+        order = wl.rotation_order(k, P)
+        xf = [oracle.pack(O, t) for t in xs]
+        wf, vf = oracle.pack(O, w), oracle.pack(O, v)
+        xd = [gh.to_dev(x) for x in xf]
+        wd_, vd = gh.to_dev(wf), gh.to_dev(vf)
+        gd = gh.dev_empty(L.N)
+        print(f"spec policy={policy} sweep={sweep} shape={shape}", flush=True)
+        mc.reduce_update_ex(L, [x.data_ptr() for x in xd], order, gd.data_ptr(), wd_.data_ptr(), vd.data_ptr(),
+                            mc.update_spec(0.1, 0.9, 1e-4, state_policy=policy, sweep=sweep), gh.stream_handle())
+        torch.cuda.synchronize()
+        g = oracle.reduce_update(O, xf, wf, vf, 0.1, 0.9, 1e-4, order=order)
+        gh.assert_bits(gd[:L.N].cpu().numpy(), g, "g")
+        gh.assert_bits(wd_.cpu().numpy(), wf, "w")
+        gh.assert_bits(vd.cpu().numpy(), vf, "v")
+        # the fused form with the same spec
+        fs = gh.FusedStep(sizes, k)
+        gpu, ref = fs.run(xs, w, v, 0.1, 0.9, 1e-4, order=order, misalign=[0],
+                          spec=mc.update_spec(0.1, 0.9, 1e-4, state_policy=policy, sweep=sweep))
+        fs.check(gpu, ref, "fused with spec")
+    finally:
+        mc.set_option(mc.OPT_RU_SHAPE, keep)
 
 
 @pytest.mark.parametrize("run", [2, 5, 16, 64])

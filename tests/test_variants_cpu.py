@@ -140,6 +140,9 @@ def test_library_schedule_and_spec_reject():
         return mc.OK
     assert code(mc.reduce_update_ex, L, x, None, g, w, v, None) == mc.ERR_INVALID_ARG
     assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(0.1, 0.9, 0.0, nesterov=2)) == mc.ERR_INVALID_ARG
+    assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(0.1, 0.9, 0.0, state_policy=3)) == mc.ERR_INVALID_ARG
+    assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(0.1, 0.9, 0.0, state_policy=-1)) == mc.ERR_INVALID_ARG
+    assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(0.1, 0.9, 0.0, sweep=3)) == mc.ERR_INVALID_ARG
     assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(hyper_dev_ptr=B + 2)) == mc.ERR_ALIGN
     assert code(mc.reduce_update_ex, L, x, None, g, w + 4, v, mc.update_spec(0.1, 0.9, 0.0)) == mc.ERR_ALIGN
     assert code(mc.reduce_update_ex, L, x, None, g, w, v, mc.update_spec(0.1, 0.9, 0.0), elem_begin=100) == mc.ERR_INVALID_ARG
