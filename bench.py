@@ -12,16 +12,23 @@ The layout (a1) is built once per model, like the framework's flattening of its 
 its cost is reported separately as `layout_create_ms`.
 
 Prints ONE JSON line.  `value` is algorithmic bytes of the whole step / wall time of the
-step; `roofline` is for the dominant kernel (fused_step_kernel, or reduce_update_kernel with
---path staged), timed with events on the stream it is launched on, inside the timed region; `cpu_baseline` is the CPU oracle timed
-on this machine's host cores on the same workload.
+step on the headline workload with steps launched back to back ("warm": weights and momentum
+of a ResNet-50-sized model stay in the 256 MB memory-side cache between steps).
+`roofline` is for the dominant kernel, timed with events on the stream it is launched on,
+inside the timed region.  `roofline_cold` is the same step when nothing of the previous step is
+still cached -- weights, momentum and g rotate over enough buffer sets to exceed the cache,
+as after the forward / backward pass that separates two steps of real training.
+`workloads` holds the other four configurations (fused step, first step checked against the
+oracle).  `cpu_baseline` is the CPU oracle timed on this machine's host cores on the headline workload.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
 import threading
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -30,20 +37,44 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+CACHE_BYTES = 256 << 20    # memory-side cache
 METRIC = "effective HBM GB/s (% of MI355X peak) and ms per ResNet-50-shaped reduce+update"
+WORKLOADS = ["tiny", "resnet50", "resnet50_heavy", "vgg16", "googlenet"]
 
 
-def measured_traffic(kernel, workload, P, k):
-    """HBM-side bytes per launch of the dominant kernel, from the rocprofv3 counter runs whose
-    summary is kept under profiles/ (None when there is none for this kernel and workload)."""
+def progress(msg):
+    """One line per phase on stderr, so that a long default run is visibly alive."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def csrc_digest():
+    """Hash of the kernel sources: a counter profile is only quoted while it matches them."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_1711_00705_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def traffic_from_profile(kernel, workload, P, k):
+    """HBM-side bytes per launch of the dominant kernel from the rocprofv3 counter runs whose
+    summary is kept under profiles/ -- or None when there is no summary for this kernel and
+    workload, or when the kernel sources have changed since it was taken."""
     path = os.path.join(ROOT, "profiles", f"{kernel.replace('_kernel', '')}_{workload}_P{P}_k{k}.txt")
+    traffic = digest = None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return int(line.split(":")[1])
+                traffic = int(line.split(":")[1])
+            if line.startswith("csrc_digest:"):
+                digest = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no counter profile for this kernel and workload"
+    if digest != csrc_digest():
+        return None, f"{os.path.relpath(path, ROOT)} was taken with other kernel sources (digest {digest})"
+    return traffic, os.path.relpath(path, ROOT)
 
 
 def parse():
@@ -51,8 +82,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="resnet50",
-                    choices=["tiny", "resnet50", "resnet50_heavy", "vgg16", "googlenet"])
+    ap.add_argument("--workload", default="resnet50", choices=WORKLOADS)
     ap.add_argument("--sets", type=int, default=0,
                     help="rotating sets of contribution tensors (0 = pick so that no step re-reads a cached set)")
     ap.add_argument("--order", default="rotation", choices=["identity", "rotation"])
@@ -60,30 +90,235 @@ def parse():
                     help="fused: one mc_fused_step per step; staged: P packs + reduce_update + unpack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--only-headline", action="store_true",
+                    help="skip the cold pass, the roles figures and the other four workloads")
     ap.add_argument("--pipeline-packets", type=int, default=0,
                     help="also run the packet-pipelined experiment with this many packets per colour")
-    ap.add_argument("--roles-nodes", type=int, default=0,
-                    help="also time one rank's role-dependent step in a tree Allreduce over this many nodes")
-    ap.add_argument("--unroll", type=int, default=0, choices=[0, 1, 2],
-                    help="16-byte vectors per thread per tile (0 = the library picks from the size)")
-    ap.add_argument("--state-store-sc1", type=int, default=-1, choices=[-1, 0, 1],
-                    help="store policy of weights / momentum (-1 = the library's default)")
-    ap.add_argument("--alternate-sweep", type=int, default=-1, choices=[-1, 0, 1],
-                    help="alternate the sweep direction between steps (-1 = the library's default)")
-    ap.add_argument("--xcd-run", type=int, default=-1,
-                    help="consecutive tiles per die, 0..64 (-1 = the library's default)")
+    ap.add_argument("--roles-nodes", type=int, default=8,
+                    help="time one rank's role-dependent step in a tree Allreduce over this many nodes (0 = skip)")
+    ap.add_argument("--shape", type=int, default=0,
+                    help="workgroup shape of the update kernels (0 = the library picks)")
+    ap.add_argument("--state-policy", type=int, default=0, choices=[0, 1, 2],
+                    help="what the default state policy means (0 = by size, 1 resident, 2 streaming)")
+    ap.add_argument("--state-store-sc1", type=int, default=-1, choices=[-1, 0, 1])
+    ap.add_argument("--alternate-sweep", type=int, default=-1, choices=[-1, 0, 1])
+    ap.add_argument("--direct-tiles", type=int, default=-1, choices=[-1, 0, 1])
+    ap.add_argument("--xcd-run", type=int, default=-1)
+    ap.add_argument("--xcd-run-pack", type=int, default=-2)
+    ap.add_argument("--xcd-run-unpack", type=int, default=-2)
     ap.add_argument("--kernel-only", action="store_true",
-                    help="time only mc_reduce_update launches (for profiler runs)")
+                    help="time only the dominant kernel's launches (for profiler runs)")
+    ap.add_argument("--cold", action="store_true",
+                    help="with --kernel-only: launch the cold-state form (rotating state sets, streaming hint)")
     return ap.parse_args()
 
 
-def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, step_bytes):
-    """The oracle as it stands: whole step (P packs, reduce+update, unpack) on host cores.
-    Its GB/s uses the same step_bytes as the GPU figure beside it, so that the ratio of the
-    two values is the ratio of the step times."""
+# ------------------------------------------------------------------------------------------
+class Harness:
+    """torch supplies device memory and the stream; everything timed is the library's."""
+
+    def __init__(self, torch, mc, wl, args):
+        self.torch, self.mc, self.wl, self.args = torch, mc, wl, args
+        self.stream = torch.cuda.current_stream()
+        self.sh = int(self.stream.cuda_stream)
+        self.pool = ThreadPoolExecutor(max_workers=8)
+
+    def upload(self, layers):
+        return [self.torch.from_numpy(t).cuda() for t in layers]
+
+    def host_set(self, cfg, step):
+        """Contributions 0..P-1 of one step, generated on host threads (numpy releases the GIL)."""
+        return list(self.pool.map(
+            lambda p: self.wl.contribution_tensors(cfg.sizes, p, step=step, heavy_tail=cfg.heavy_tail), range(cfg.P)))
+
+    def events(self):
+        return self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+
+    def time_region(self, fn, warmup, steps):
+        """W untimed calls, then EXACTLY `steps` timed ones bracketed by synchronisation.  Returns
+        (ms per call by the host clock, ms per call by one HIP event pair around the region on the
+        launch stream): back-to-back launches, no event packets between them."""
+        torch = self.torch
+        for i in range(warmup):
+            fn(i)
+        a, b = self.events()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a.record(self.stream)
+        for i in range(steps):
+            fn(warmup + i)
+        b.record(self.stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return wall, a.elapsed_time(b) / steps
+
+    def time_each(self, fn, warmup, steps):
+        """One event pair per call (adds a few microseconds to each): for medians and minima."""
+        for i in range(warmup):
+            fn(i)
+        evs = [self.events() for _ in range(steps)]
+        self.torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            a.record(self.stream)
+            fn(warmup + i)
+            b.record(self.stream)
+        self.torch.cuda.synchronize()
+        return np.array([a.elapsed_time(b) for a, b in evs])
+
+
+class Inputs:
+    """One workload resident in HBM: n_sets rotating contribution sets as per-layer tensors."""
+
+    def __init__(self, H, cfg, n_sets, keep_host_sets):
+        mc, wl = H.mc, H.wl
+        self.cfg, self.n_sets = cfg, n_sets
+        t0 = time.perf_counter()
+        self.L = mc.Layout(cfg.sizes, cfg.k)
+        self.layout_ms = (time.perf_counter() - t0) * 1e3
+        self.L.prepare()
+        self.host_sets, self.dev_sets, self.tables, self.tsets = [], [], [], []
+        for s in range(n_sets):
+            per_p = H.host_set(cfg, s)
+            if s < keep_host_sets:
+                self.host_sets.append(per_p)
+            dev = [H.upload(ts) for ts in per_p]
+            self.dev_sets.append(dev)
+            self.tables.append([mc.ptr_table([t.data_ptr() for t in d]) for d in dev])
+            self.tsets.append(mc.set_table([mc.TensorSet(self.L, [t.data_ptr() for t in d]) for d in dev]))
+        self.w_host = wl.weight_tensors(cfg.sizes)
+
+    def state_set(self, H):
+        """Per-layer weights (seeded) and zero momentum, with their tensor sets."""
+        w = H.upload(self.w_host)
+        v = [H.torch.zeros_like(t) for t in w]
+        return dict(w=w, v=v, wset=H.mc.TensorSet(self.L, [t.data_ptr() for t in w]),
+                    vset=H.mc.TensorSet(self.L, [t.data_ptr() for t in v]))
+
+
+def n_sets_for(cfg, args):
+    set_bytes = 4 * cfg.total * cfg.P
+    # enough rotating sets that a step never finds its contributions in the memory-side cache
+    n = args.sets or (cfg.steps if cfg.steps > 1 else max(3, int(np.ceil(1.2e9 / set_bytes))))
+    return min(n, 100)
+
+
+def oracle_first_step(cfg, order, host_set, w_host):
+    """The oracle's pack x P -> reduce_update -> unpack on the first contribution set."""
+    import oracle
+    O = oracle.Layout(cfg.sizes, cfg.k)
+    w = oracle.pack(O, w_host)
+    v = np.zeros(O.N, np.float32)
+    xs = [oracle.pack(O, ts) for ts in host_set]
+    g = oracle.reduce_update(O, xs, w, v, cfg.lr, cfg.mu, cfg.wd, order=order)
+    return dict(g=g, w=w, v=v, w_layers=oracle.unpack(O, w), v_layers=oracle.unpack(O, v))
+
+
+def same_bits(a, b):
+    return np.array_equal(np.ascontiguousarray(a).view(np.uint32), np.ascontiguousarray(b).view(np.uint32))
+
+
+def fused_parity(H, I, order, ref):
+    """One mc_fused_step from the seeded initial state on set 0, compared bit for bit."""
+    cfg, mc, torch = I.cfg, H.mc, H.torch
+    st = I.state_set(H)
+    g = torch.empty(cfg.total, dtype=torch.float32, device="cuda")
+    mc.fused_step(I.L, I.tsets[0], order, g.data_ptr(), st["wset"], st["vset"], cfg.lr, cfg.mu, cfg.wd, H.sh)
+    torch.cuda.synchronize()
+    bad = []
+    if not same_bits(g.cpu().numpy(), ref["g"]):
+        bad.append("fused g")
+    for key, layers in (("w", st["w"]), ("v", st["v"])):
+        if not all(same_bits(a.cpu().numpy(), b) for a, b in zip(layers, ref[key + "_layers"])):
+            bad.append("fused " + key)
+    return bad
+
+
+def cold_pass(H, I, order, steps, warmup):
+    """The fused step with nothing left in the caches from the step before: weights, momentum and g
+    rotate over enough sets to exceed three times the memory-side cache (contributions rotate anyway).
+    Timed with the state policy a caller would pass when a forward / backward pass separates the
+    steps (streaming) and, for comparison, with the policy that suits back-to-back steps (resident)."""
+    cfg, mc, torch = I.cfg, H.mc, H.torch
+    N, P = cfg.total, cfg.P
+    n_state = max(4, int(np.ceil(3 * CACHE_BYTES / (8 * N))))
+    n_g = max(4, int(np.ceil(3 * CACHE_BYTES / (4 * N))))
+    states = [I.state_set(H) for _ in range(n_state)]
+    gs = [torch.empty(N, dtype=torch.float32, device="cuda") for _ in range(n_g)]
+    bytes_ = 4 * (P + 5) * N
+    out = {"state_sets": n_state, "g_buffers": n_g, "contribution_sets": I.n_sets}
+    for name, policy in (("streaming", mc.STATE_STREAMING), ("resident", mc.STATE_RESIDENT)):
+        spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd, state_policy=policy, sweep=mc.SWEEP_FORWARD)
+
+        def step(i):
+            st = states[i % n_state]
+            mc.fused_step_ex(I.L, I.tsets[i % I.n_sets], order, gs[i % n_g].data_ptr(), st["wset"], st["vset"],
+                             spec, H.sh)
+        wall, ev = H.time_region(step, warmup, steps)
+        out[name] = {"ms_per_step": round(wall, 4), "kernel_ms": round(ev, 4),
+                     "GBps": round(bytes_ / ev / 1e6, 1), "frac": round(bytes_ / ev / 1e6 / HBM_PEAK_GBPS, 4)}
+    return out, states, gs
+
+
+def run_other_workload(H, name, order_kind, check_parity):
+    """Fused step of one of the non-headline configurations: first step against the oracle, then
+    W warm-up + K timed back-to-back steps over rotating contribution sets."""
+    mc, wl, torch = H.mc, H.wl, H.torch
+    cfg = wl.workload(name)
+    N, P, k = cfg.total, cfg.P, cfg.k
+    order = None if order_kind == "identity" else wl.rotation_order(k, P)
+    n_sets = n_sets_for(cfg, H.args)
+    if name == "vgg16":
+        n_sets = 2                      # 2.2 GB per set: two already exceed the cache many times over
+    K, W = {"tiny": (200, 20), "resnet50": (50, 10), "resnet50_heavy": (50, 10), "vgg16": (20, 5),
+            "googlenet": (100, 10)}[name]
+    progress(f"{name}: generating and uploading {n_sets} contribution sets")
+    t0 = time.perf_counter()
+    I = Inputs(H, cfg, n_sets, keep_host_sets=1)
+    setup_s = time.perf_counter() - t0
+    progress(f"{name}: parity of the first step, then {W} + {K} steps")
+    out = {"config": f"{cfg.n_tensors} tensors, N={N} fp32, P={P}, k={k}, lr={cfg.lr} mu={cfg.mu} wd={cfg.wd}, "
+                     f"order={order_kind}, {n_sets} rotating contribution sets",
+           "steps": K, "warmup": W}
+    if check_parity:
+        ref = oracle_first_step(cfg, order, I.host_sets[0], I.w_host)
+        bad = fused_parity(H, I, order, ref)
+        if bad:
+            print(f"bench.py: PARITY FAILURE against the oracle on {name}: {bad}", file=sys.stderr)
+            sys.exit(4)
+        out["parity_first_step"] = True
+    else:
+        out["parity_first_step"] = None
+    I.host_sets = None
+    st = I.state_set(H)
+    g = torch.empty(N, dtype=torch.float32, device="cuda")
+    bytes_ = 4 * (P + 5) * N
+
+    def step(i):
+        mc.fused_step(I.L, I.tsets[i % n_sets], order, g.data_ptr(), st["wset"], st["vset"], cfg.lr, cfg.mu, cfg.wd, H.sh)
+    wall, ev = H.time_region(step, W, K)
+    state_bytes = 8 * N
+    out.update({"ms_per_step": round(wall, 4), "kernel_ms": round(ev, 4), "step_bytes": bytes_,
+                "GBps": round(bytes_ / wall / 1e6, 1), "frac": round(bytes_ / ev / 1e6 / HBM_PEAK_GBPS, 4),
+                "state": ("weights + momentum (%d MB) exceed the memory-side cache: streamed" % (state_bytes >> 20))
+                if state_bytes > CACHE_BYTES else
+                ("weights + momentum (%d MB) stay cache-resident between back-to-back steps" % (state_bytes >> 20)),
+                "setup_s": round(setup_s, 1)})
+    if state_bytes <= CACHE_BYTES and name != "tiny":
+        cold, states, gs = cold_pass(H, I, order, K, W)
+        out["cold"] = cold
+        del states, gs
+    del I, st, g
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, gpu_step_ms):
+    """The oracle as it stands: whole step (P packs, reduce+update, unpack) on host cores.  Its GB/s is
+    over the bytes the oracle itself moves, (8P + 4(P+5) + 8) * N per step."""
     import oracle
     O = oracle.Layout(cfg.sizes, cfg.k)
     N = O.N
+    moved = (8 * cfg.P + 4 * (cfg.P + 5) + 8) * N
     w = oracle.pack(O, w_layers_host)
     v = np.zeros(N, np.float32)
 
@@ -137,46 +372,38 @@ def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, step
         threaded_step(s)
     dt2 = (time.perf_counter() - t0) / n2
     return {
-        "value": round(step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "ms_per_step": round(dt * 1e3, 3),
+        "value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "ms_per_step": round(dt * 1e3, 3), "bytes_moved_per_step": moved,
+        "step_time_ratio_vs_gpu": round(dt * 1e3 / gpu_step_ms, 1) if gpu_step_ms else None,
         "sample": f"{n} whole steps ({cfg.P} packs + reduce+update + unpack) of the full {cfg.name} "
                   f"workload, N={N}, single thread",
-        "threaded": {"value": round(step_bytes / dt2 / 1e9, 3), "unit": "GB/s",
+        "threaded": {"value": round(moved / dt2 / 1e9, 3), "unit": "GB/s",
                      "cores": max(nthr, min(cfg.P, ncpu)), "ms_per_step": round(dt2 * 1e3, 3),
                      "sample": f"{n2} whole steps, one host thread per colour ({nthr}) / per pack ({cfg.P})"},
         "host_cpus": ncpu,
     }
 
 
-def roles_experiment(torch, mc, L, cfg, flats, g, w, v, stream, n_nodes, reps):
+def roles_experiment(H, L, cfg, flats, g, w, v, n_nodes, reps):
     """One rank's real share in a k-colour tree Allreduce over n_nodes nodes (Section 4.2): it
     is inner node or root of at most one colour and a leaf of the others.  Phase 1: per colour,
     add the m local replicas (leaf) or those plus one buffer per child (inner node, root); only
-    the root's colour is updated at once.  Phase 2: the other colours are updated from the
-    broadcast sum (a single contribution).  m = the workload's P; child buffers are further
-    flat buffers of the same size.  Times both phases for the rank with the most work (an inner
-    node) and for a pure-leaf rank, with the algorithmic bytes of each."""
+    the root's colour is updated at once -- one launch whatever the mix.  Phase 2: the other colours
+    are updated from the broadcast sum (a single contribution).  m = the workload's P; child
+    buffers are further flat buffers of the same size.  Times both phases for one rank of each
+    kind, with the algorithmic bytes of each."""
+    torch, mc = H.torch, H.mc
     N, m, k = cfg.total, cfg.P, cfg.k
-    sh = int(stream.cuda_stream)
     bounds = [int(b) for b in L.colour_bounds()]
     lens = [bounds[c + 1] - bounds[c] for c in range(k)]
     child_bufs = [torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3 for _ in range(k)]
     contrib = mc.ptr_table([f.data_ptr() for f in flats] + [c.data_ptr() for c in child_bufs])
     bcast = torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3
     bcast_tab = mc.ptr_table([bcast.data_ptr()])
-    scratch = torch.empty(N, dtype=torch.float32, device="cuda")
 
     def timed(fn):
-        fn()
-        torch.cuda.synchronize()
-        a = torch.cuda.Event(enable_timing=True)
-        b = torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        for _ in range(reps):
-            fn()
-        b.record(stream)
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
+        _, ev = H.time_region(lambda i: fn(), 2, reps)
+        return ev
 
     out = {"n_nodes": n_nodes, "colours": k, "local_replicas": m, "ranks": {}}
     picked = {}
@@ -191,9 +418,10 @@ def roles_experiment(torch, mc, L, cfg, flats, g, w, v, stream, n_nodes, reps):
         bytes1 = sum(4 * lens[c] * (n_terms[c] + 1 + (4 if upd[c] else 0)) for c in range(k))
         bytes2 = sum(4 * lens[c] * (1 + 4) for c in range(k) if later[c])
         t1 = timed(lambda: mc.reduce_update_roles(L, contrib, None, n_terms, upd, g.data_ptr(), w.data_ptr(),
-                                                  v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, sh))
-        t2 = timed(lambda: mc.reduce_update_roles(L, bcast_tab, None, later, [1] * k, scratch.data_ptr(),
-                                                  w.data_ptr(), v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, sh)) \
+                                                  v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, H.sh))
+        # every colour of this call updates, so no grad_out is needed
+        t2 = timed(lambda: mc.reduce_update_roles(L, bcast_tab, None, later, [1] * k, None,
+                                                  w.data_ptr(), v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, H.sh)) \
             if any(later) else 0.0
         out["ranks"][kind] = {"rank": rank, "terms_per_colour": n_terms, "updates_at_once": upd,
                               "sum_ms": round(t1, 4), "sum_GBps": round(bytes1 / t1 / 1e6, 1),
@@ -202,7 +430,7 @@ def roles_experiment(torch, mc, L, cfg, flats, g, w, v, stream, n_nodes, reps):
     return out
 
 
-def pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, stream, packets, reps):
+def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, reps):
     """Section 4.2 pipelines the reductions packet by packet.  Here half of the P contributions
     are resident and the other half "arrive": staging copies on a second stream stand in for
     network buffers landing in the receive buffers.  Unpipelined: all copies, then one
@@ -210,11 +438,11 @@ def pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, st
     concurrently), copy the packet of every arriving contribution, then mc_reduce_update_range
     on it as soon as its copies are done.  On one GPU copies and sum share the same HBM, so
     this measures latency hiding, not extra bandwidth."""
+    torch, mc, stream = H.torch, H.mc, H.stream
     N, P, k = cfg.total, cfg.P, cfg.k
     arriving = list(range(P // 2, P))
     src = [torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3 for _ in arriving]
     copy_stream = torch.cuda.Stream()
-    sh = int(stream.cuda_stream)
     bounds = [int(b) for b in L.colour_bounds()]
     pk = []
     for c in range(k):
@@ -252,16 +480,8 @@ def pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, st
                          cfg.lr, cfg.mu, cfg.wd, int(main.cuda_stream))
 
     def timed(fn):
-        fn()
-        torch.cuda.synchronize()
-        a = torch.cuda.Event(enable_timing=True)
-        b = torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        for _ in range(reps):
-            fn()
-        b.record(stream)
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
+        _, ev = H.time_region(lambda i: fn(), 1, reps)
+        return ev
 
     def captured(fn):
         """The same sequence captured once into a HIP graph (kernel nodes and event edges only)
@@ -299,48 +519,38 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    if args.unroll:
-        mc.set_option(mc.OPT_RU_SHAPE, args.unroll)
+    if args.shape:
+        mc.set_option(mc.OPT_RU_SHAPE, args.shape)
+    if args.state_policy:
+        mc.set_option(mc.OPT_STATE_POLICY, args.state_policy)
     if args.alternate_sweep >= 0:
         mc.set_option(mc.OPT_ALTERNATE_SWEEP, args.alternate_sweep)
     if args.state_store_sc1 >= 0:
         mc.set_option(mc.OPT_STATE_STORE_SC1, args.state_store_sc1)
+    if args.direct_tiles >= 0:
+        mc.set_option(mc.OPT_DIRECT_TILES, args.direct_tiles)
     if args.xcd_run >= 0:
         mc.set_option(mc.OPT_XCD_RUN, args.xcd_run)
+    if args.xcd_run_pack >= -1:
+        mc.set_option(mc.OPT_XCD_RUN_PACK, args.xcd_run_pack)
+    if args.xcd_run_unpack >= -1:
+        mc.set_option(mc.OPT_XCD_RUN_UNPACK, args.xcd_run_unpack)
+    H = Harness(torch, mc, wl, args)
+    stream, sh = H.stream, H.sh
     cfg = wl.workload(args.workload)
     N, P, k = cfg.total, cfg.P, cfg.k
     order = None if args.order == "identity" else wl.rotation_order(k, P)
-    set_bytes = 4 * N * P
-    # enough rotating sets that a step never finds its contributions in the 256 MB last-level cache
-    n_sets = args.sets or (cfg.steps if cfg.steps > 1 else max(3, int(np.ceil(1.2e9 / set_bytes))))
-    n_sets = min(n_sets, 100)
-
-    t0 = time.perf_counter()
-    L = mc.Layout(cfg.sizes, k)
-    layout_ms = (time.perf_counter() - t0) * 1e3
-    L.prepare()
-    stream = torch.cuda.current_stream()
-    sh = int(stream.cuda_stream)
-
-    def upload(layers):
-        return [torch.from_numpy(t).cuda() for t in layers]
+    n_sets = n_sets_for(cfg, args)
 
     # ---- inputs: seeded, host-generated, uploaded as separate per-layer tensors ------------
-    host_sets = []            # kept for the CPU baseline (first 3 sets only)
-    dev_sets, tables, tsets = [], [], []
-    for s in range(n_sets):
-        per_p = [wl.contribution_tensors(cfg.sizes, p, step=s, heavy_tail=cfg.heavy_tail) for p in range(P)]
-        if s < 3:
-            host_sets.append(per_p)
-        dev = [upload(ts) for ts in per_p]
-        dev_sets.append(dev)
-        tables.append([mc.ptr_table([t.data_ptr() for t in d]) for d in dev])
-        tsets.append(mc.set_table([mc.TensorSet(L, [t.data_ptr() for t in d]) for d in dev]))
-    w_layers_host = wl.weight_tensors(cfg.sizes)
+    progress(f"{cfg.name}: generating and uploading {n_sets} contribution sets")
+    I = Inputs(H, cfg, n_sets, keep_host_sets=3)
+    L, tables, tsets = I.L, I.tables, I.tsets
+    w_layers_host = I.w_host
     g = torch.empty(N, dtype=torch.float32, device="cuda")
 
     # staged path state: flat w, v (master), per-layer weights as the unpack destination
-    w_layers = upload(w_layers_host)
+    w_layers = H.upload(w_layers_host)
     w_table = mc.ptr_table([t.data_ptr() for t in w_layers])
     flats = [torch.empty(N, dtype=torch.float32, device="cuda") for _ in range(P)]
     flat_table = mc.ptr_table([f.data_ptr() for f in flats])
@@ -349,10 +559,8 @@ def main():
     mc.pack(L, w_table, w.data_ptr(), sh)
 
     # fused path state: per-layer weights and momentum, updated in place
-    fw_layers = upload(w_layers_host)
-    fv_layers = [torch.zeros_like(t) for t in fw_layers]
-    fw_set = mc.TensorSet(L, [t.data_ptr() for t in fw_layers])
-    fv_set = mc.TensorSet(L, [t.data_ptr() for t in fv_layers])
+    fst = I.state_set(H)
+    fw_layers, fv_layers, fw_set, fv_set = fst["w"], fst["v"], fst["wset"], fst["vset"]
     torch.cuda.synchronize()
 
     def staged_step(i, ev=None):
@@ -367,21 +575,44 @@ def main():
             ev[1].record(stream)
         mc.unpack(L, w.data_ptr(), w_table, sh)
 
-    def fused_step(i, ev=None):
-        if ev:
-            ev[0].record(stream)
+    def fused_step(i):
         mc.fused_step(L, tsets[i % n_sets], order, g.data_ptr(), fw_set, fv_set, cfg.lr, cfg.mu, cfg.wd, sh)
-        if ev:
-            ev[1].record(stream)
 
     fused = args.path == "fused"
-    step = fused_step if fused else staged_step
     kernel_name = "fused_step_kernel" if fused else "reduce_update_kernel"
     kernel_bytes = 4 * (P + 5) * N        # P reads + w, v read and written + g written: same for both kernels
-    step_bytes = kernel_bytes if fused else (8 * P + 4 * (P + 5) + 8) * N
+    staged_bytes = (8 * P + 4 * (P + 5) + 8) * N
+    step_bytes = kernel_bytes if fused else staged_bytes
 
+    if args.kernel_only:
+        if args.cold:
+            n_state = max(4, int(np.ceil(3 * CACHE_BYTES / (8 * N))))
+            states = [I.state_set(H) for _ in range(n_state)]
+            gs = [torch.empty(N, dtype=torch.float32, device="cuda") for _ in range(4)]
+            spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd, state_policy=mc.STATE_STREAMING, sweep=mc.SWEEP_FORWARD)
+
+            def kernel_launch(i):
+                st = states[i % n_state]
+                mc.fused_step_ex(L, tsets[i % n_sets], order, gs[i % 4].data_ptr(), st["wset"], st["vset"], spec, sh)
+        elif fused:
+            kernel_launch = fused_step
+        else:
+            def kernel_launch(i):
+                mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                                 cfg.lr, cfg.mu, cfg.wd, sh)
+        wall, ev = H.time_region(kernel_launch, args.warmup, args.steps)
+        # known-size traffic for counter calibration: copy_kernel moves copy_bytes each way
+        copy_bytes = (N // 4) * 16
+        for i in range(3):
+            mc.copy(flats[0].data_ptr(), g.data_ptr(), copy_bytes, sh)
+        torch.cuda.synchronize()
+        print(json.dumps({"kernel": kernel_name, "cold": bool(args.cold), "kernel_only_ms": ev,
+                          "GBps": kernel_bytes / ev / 1e6, "kernel_bytes": kernel_bytes,
+                          "copy_bytes_each_way": copy_bytes}))
+        return
+
+    progress(f"{cfg.name}: first steps, then {args.warmup} + {args.steps} timed steps of both forms")
     # ---- parity of the very first step of BOTH paths against the oracle (same host bytes) ----
-    parity_ref, cpu = {}, None
     staged_step(0)
     torch.cuda.synchronize()
     first = dict(g=g.cpu().numpy(), w=w.cpu().numpy(), v=v.cpu().numpy())
@@ -389,120 +620,74 @@ def main():
     torch.cuda.synchronize()
     first_fused = dict(g=g.cpu().numpy(), w=[t.cpu().numpy() for t in fw_layers],
                        v=[t.cpu().numpy() for t in fv_layers])
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, order, host_sets, w_layers_host, args.cpu_seconds, parity_ref, step_bytes)
-        import oracle
-        O = oracle.Layout(cfg.sizes, k)
-        ref_layers = dict(w=oracle.unpack(O, parity_ref["w"]), v=oracle.unpack(O, parity_ref["v"]))
-        bad = [key for key in ("g", "w", "v")
-               if not np.array_equal(first[key].view(np.uint32), parity_ref[key].view(np.uint32))]
-        if not np.array_equal(first_fused["g"].view(np.uint32), parity_ref["g"].view(np.uint32)):
-            bad.append("fused g")
-        for key in ("w", "v"):
-            for a, b in zip(first_fused[key], ref_layers[key]):
-                if not np.array_equal(a.view(np.uint32), b.view(np.uint32)):
-                    bad.append("fused " + key)
-                    break
-        if bad:
-            print(f"bench.py: PARITY FAILURE against the oracle on {bad}", file=sys.stderr)
-            sys.exit(4)
-    host_sets = None
 
-    def kernel_launch(i):
-        if fused:
-            mc.fused_step(L, tsets[i % n_sets], order, g.data_ptr(), fw_set, fv_set, cfg.lr, cfg.mu, cfg.wd, sh)
-        else:
-            mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
-                             cfg.lr, cfg.mu, cfg.wd, sh)
-
-    if args.kernel_only:
-        for i in range(args.warmup):
-            kernel_launch(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            kernel_launch(args.warmup + i)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        # known-size traffic for counter calibration: copy_kernel moves copy_bytes each way
-        copy_bytes = (N // 4) * 16
-        for i in range(3):
-            mc.copy(flats[0].data_ptr(), g.data_ptr(), copy_bytes, sh)
-        torch.cuda.synchronize()
-        print(json.dumps({"kernel": kernel_name, "kernel_only_ms": ms, "GBps": kernel_bytes / ms / 1e6,
-                          "kernel_bytes": kernel_bytes, "copy_bytes_each_way": copy_bytes}))
-        return
-
-    def timed_steps(fn, warmup, steps, per_step_events):
-        """W untimed steps, then EXACTLY `steps` timed ones.  Returns (ms per step by the host
-        clock, launch durations of the dominant kernel in ms by HIP events on the launch
-        stream).  Staged path: one event pair around reduce_update in every step.  Fused
-        path: the step IS the kernel, launched back to back, so one pair around the whole
-        timed region gives its average duration (dispatch gaps included) without putting
-        event packets between the launches."""
+    # ---- timing of both forms of the step ---------------------------------------------------
+    def timed_staged(warmup, steps):
+        """Host clock around K whole staged steps after W untimed ones, one event pair around
+        reduce_update in each."""
         for i in range(warmup):
-            fn(i + 1)
-        if per_step_events:
-            events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                      for _ in range(steps)]
-        else:
-            span = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            staged_step(i + 1)
+        evs = [H.events() for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        if not per_step_events:
-            span[0].record(stream)
         for i in range(steps):
-            fn(warmup + 1 + i, events[i] if per_step_events else None)
-        if not per_step_events:
-            span[1].record(stream)
+            staged_step(warmup + 1 + i, evs[i])
         torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        if per_step_events:
-            return wall * 1e3 / steps, np.array([a.elapsed_time(b) for a, b in events])
-        return wall * 1e3 / steps, np.array([span[0].elapsed_time(span[1]) / steps])
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return wall, np.array([a.elapsed_time(b) for a, b in evs])
 
-    ms_per_step, k_ms = timed_steps(step, args.warmup, args.steps, per_step_events=not fused)
-    other_ms, other_k_ms = timed_steps(staged_step if fused else fused_step, args.warmup, args.steps,
-                                       per_step_events=fused)
+    fused_ms, fused_k = H.time_region(lambda i: fused_step(i + 1), args.warmup, args.steps)
+    staged_ms, staged_k = timed_staged(args.warmup, args.steps)
+    ms_per_step = fused_ms if fused else staged_ms
+    k_avg = fused_k if fused else float(staged_k.mean())
 
     # Median and minimum of single launches of the fused kernel, from one event pair per launch in a
     # separate untimed pass (the event packets between launches add a few microseconds to each, which
     # is why the timed region above brackets all its launches with one pair instead).
-    _, fused_each = timed_steps(fused_step, 2, max(10, min(args.steps, 100)), per_step_events=True)
+    fused_each = H.time_each(lambda i: fused_step(i + 1), 2, max(10, min(args.steps, 100)))
 
     # ---- the pieces on their own (events around back-to-back launches), and the copy yardstick
-    def timed(fn, reps):
-        a = torch.cuda.Event(enable_timing=True)
-        b = torch.cuda.Event(enable_timing=True)
-        fn(0)
-        torch.cuda.synchronize()
-        a.record(stream)
-        for r in range(reps):
-            fn(r + 1)
-        b.record(stream)
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
-
     reps = max(10, min(args.steps, 50))
-    pack_ms = timed(lambda r: mc.pack(L, tables[r % n_sets][r % P], flats[r % P].data_ptr(), sh), reps)
-    unpack_ms = timed(lambda r: mc.unpack(L, w.data_ptr(), w_table, sh), reps)
-    copy_ms = timed(lambda r: mc.copy(flats[r % P].data_ptr(), flats[(r + 1) % P].data_ptr(), 4 * (N // 4) * 4, sh), reps)
+    _, pack_ms = H.time_region(lambda r: mc.pack(L, tables[r % n_sets][r % P], flats[r % P].data_ptr(), sh), 1, reps)
+    _, unpack_ms = H.time_region(lambda r: mc.unpack(L, w.data_ptr(), w_table, sh), 1, reps)
+    _, copy_ms = H.time_region(lambda r: mc.copy(flats[r % P].data_ptr(), flats[(r + 1) % P].data_ptr(),
+                                                 4 * (N // 4) * 4, sh), 1, reps)
+
+    # ---- CPU oracle: baseline and parity reference ---------------------------------------------
+    parity_ref, cpu = {}, None
+    if not args.no_cpu_baseline:
+        progress(f"{cfg.name}: CPU oracle (baseline and parity reference), about {2 * args.cpu_seconds:.0f} s")
+        cpu = cpu_baseline(cfg, order, I.host_sets, w_layers_host, args.cpu_seconds, parity_ref, ms_per_step)
+        import oracle
+        O = oracle.Layout(cfg.sizes, k)
+        ref_layers = dict(w=oracle.unpack(O, parity_ref["w"]), v=oracle.unpack(O, parity_ref["v"]))
+        bad = [key for key in ("g", "w", "v") if not same_bits(first[key], parity_ref[key])]
+        if not same_bits(first_fused["g"], parity_ref["g"]):
+            bad.append("fused g")
+        for key in ("w", "v"):
+            if not all(same_bits(a, b) for a, b in zip(first_fused[key], ref_layers[key])):
+                bad.append("fused " + key)
+        if bad:
+            print(f"bench.py: PARITY FAILURE against the oracle on {bad}", file=sys.stderr)
+            sys.exit(4)
+    I.host_sets = None
 
     pipelined = None
     if args.pipeline_packets > 0:
-        pipelined = pipeline_experiment(torch, mc, L, cfg, order, flats, flat_table, g, w, v, stream,
+        pipelined = pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v,
                                         args.pipeline_packets, reps=max(5, min(args.steps, 30)))
+    roles = cold = None
+    others = {}
+    if not args.only_headline:
+        progress(f"{cfg.name}: roles and cold-state passes")
+        if args.roles_nodes > 0 and k * ((args.roles_nodes - 1 + k - 1) // k) <= args.roles_nodes:
+            roles = roles_experiment(H, L, cfg, flats, g, w, v, args.roles_nodes, reps=max(5, min(args.steps, 30)))
+        if 8 * N <= CACHE_BYTES:
+            cold, states, gs = cold_pass(H, I, order, args.steps, args.warmup)
+            del states, gs
 
-    roles = None
-    if args.roles_nodes > 0:
-        roles = roles_experiment(torch, mc, L, cfg, flats, g, w, v, stream, args.roles_nodes,
-                                 reps=max(5, min(args.steps, 30)))
-
-    k_avg = float(k_ms.mean())
     achieved = kernel_bytes / k_avg / 1e6
-    staged_bytes = (8 * P + 4 * (P + 5) + 8) * N
-    staged_ms, staged_k = (other_ms, other_k_ms) if fused else (ms_per_step, k_ms)
-    fused_ms, fused_k = (ms_per_step, k_ms) if fused else (other_ms, other_k_ms)
+    traffic, traffic_src = traffic_from_profile(kernel_name, cfg.name, P, k)
     out = {
         "metric": METRIC,
         "value": round(step_bytes / ms_per_step / 1e6, 1),
@@ -523,10 +708,13 @@ def main():
                    "step": ("mc_fused_step: contributions read from per-layer tensors, per-layer weights and "
                             "momentum updated in place, flat grad_out written" if fused else
                             f"{P} x mc_pack + mc_reduce_update (writes grad_out) + mc_unpack(weights)"),
-                   "step_bytes": step_bytes},
+                   "step_bytes": step_bytes,
+                   "state": "warm: steps run back to back, so weights + momentum (%d MB) %s" % (
+                       (8 * N) >> 20, "stay in the 256 MB memory-side cache between steps; see roofline_cold"
+                       if 8 * N <= CACHE_BYTES else "exceed the memory-side cache and are streamed")},
         "pct_of_hbm_peak": round(100 * step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
-        "fused_step": {"ms_per_step": round(fused_ms, 4), "kernel_ms": round(float(fused_k.mean()), 4),
-                       "GBps": round(kernel_bytes / float(fused_k.mean()) / 1e6, 1), "step_bytes": kernel_bytes,
+        "fused_step": {"ms_per_step": round(fused_ms, 4), "kernel_ms": round(fused_k, 4),
+                       "GBps": round(kernel_bytes / fused_k / 1e6, 1), "step_bytes": kernel_bytes,
                        "single_launch_ms_median": round(float(np.median(fused_each)), 4),
                        "single_launch_ms_min": round(float(fused_each.min()), 4)},
         "staged_step": {"ms_per_step": round(staged_ms, 4), "GBps": round(staged_bytes / staged_ms / 1e6, 1),
@@ -537,17 +725,35 @@ def main():
                         "pack_ms": round(pack_ms, 4), "pack_GBps": round(8 * N / pack_ms / 1e6, 1),
                         "unpack_ms": round(unpack_ms, 4), "unpack_GBps": round(8 * N / unpack_ms / 1e6, 1)},
         "copy_yardstick": {"ms": round(copy_ms, 4), "GBps": round(8 * (N // 4) * 4 / copy_ms / 1e6, 1)},
-        "layout_create_ms": round(layout_ms, 3),
+        "layout_create_ms": round(I.layout_ms, 3),
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(kernel_name, cfg.name, P, k), "bytes_per_launch": kernel_bytes,
-                     "kernel_ms": round(k_avg, 4)},
+                     "traffic": traffic, "traffic_source": traffic_src, "bytes_per_launch": kernel_bytes,
+                     "kernel_ms": round(k_avg, 4), "state": "warm"},
+        "roofline_cold": None,
         "pipelined_packets": pipelined,
         "roles": roles,
         "cpu_baseline": cpu,
         "parity_checked_first_step": cpu is not None,
         "library": os.path.relpath(mc.LIBRARY_PATH, ROOT),
     }
+    if cold is not None:
+        c = cold["streaming"]
+        out["roofline_cold"] = {"bound": "hbm", "kernel": "fused_step_kernel", "achieved": c["GBps"],
+                                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": c["frac"],
+                                "bytes_per_launch": kernel_bytes, "kernel_ms": c["kernel_ms"],
+                                "ms_per_step": c["ms_per_step"], "state_policy": "streaming",
+                                "resident_policy": cold["resident"],
+                                "rotation": {key: cold[key] for key in ("state_sets", "g_buffers", "contribution_sets")}}
+
+    if not args.only_headline:
+        # free the headline's buffers before the large configurations
+        del I, tables, tsets, flats, flat_table, w, v, g, fst, fw_layers, fv_layers, fw_set, fv_set, w_layers, w_table
+        torch.cuda.empty_cache()
+        for name in WORKLOADS:
+            if name != cfg.name:
+                others[name] = run_other_workload(H, name, args.order, check_parity=not args.no_cpu_baseline)
+    out["workloads"] = others or None
     print(json.dumps(out))
 
 

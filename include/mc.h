@@ -65,7 +65,7 @@ enum {
 #define MC_COLOUR_ALIGN_ELEMS 256   /* colour chunk length is a multiple of this (1 KiB) */
 
 /* ---- a1: layout --------------------------------------------------------------------
- * Section 4.2 ("the application payload is split into k chunks"): the payload is the dense
+ * Section 4.2 (the payload is split into k chunks, one per colour): the payload is the dense
  * concatenation of the n per-layer tensors in the given order (tensor t occupies flat
  * elements [off_t, off_t + numel[t]), off_t = numel[0] + ... + numel[t-1], N = off_n), and
  * colour c owns flat elements [b_c, b_{c+1}) with b_c = min(N, c*C),
@@ -103,7 +103,8 @@ int mc_layout_colour_bounds(const mc_layout* L, int64_t* b);
  *          tensors are ignored and may be NULL.
  * flat:    device, N fp32, 16-byte aligned.
  * Errors: MC_ERR_INVALID_ARG (NULL L / tensors / flat with N > 0 / a NULL entry of a
- * non-empty tensor), MC_ERR_ALIGN, MC_ERR_OVERLAP (a tensor overlaps flat), MC_ERR_HIP. */
+ * non-empty tensor), MC_ERR_ALIGN, MC_ERR_OVERLAP (a tensor overlaps flat; for unpack also two
+ * destination tensors that overlap each other), MC_ERR_HIP. */
 int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream);
 int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream);
 
@@ -300,6 +301,50 @@ int mc_fused_step_ex(mc_layout* L, const mc_tensor_set* const* contrib, int32_t 
                      const mc_update_spec* spec, void* stream);
 int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream);
 
+/* ---- packets consumed as they arrive: the pipelined reduction ------------------------------
+ * Section 4.2: the k reductions are pipelined, packets of all colours are in flight at once and a
+ * summing rank adds each packet when it has arrived.  mc_reduce_update_range leaves the sequencing
+ * to the caller (an event wait per packet, tens of microseconds each on this platform);
+ * mc_reduce_update_packets moves it into ONE resident kernel: its workgroups walk the packets in
+ * their order of arrival and, before touching packet j, poll the device-memory flag ready[j] until it
+ * equals ready_value.  Whatever delivers packet j -- a copy kernel, a peer GPU, a network adapter --
+ * writes the packet's data into the contribution buffers first and the flag afterwards, with release
+ * semantics at device scope; mc_packet_signal is that flag write as a kernel on a stream (ordered
+ * after everything queued on that stream before it).
+ *
+ * Every wait is bounded: a workgroup polls at most spin_limit times in total (about a microsecond
+ * apart) and then stops; no packet is ever left half-summed.  progress (device, n_blocks +
+ * MC_PACKETS_STATUS_WORDS uint32) records per workgroup how many packets it has completed; a later
+ * call with the same packets, flags, progress and n_blocks resumes every workgroup from its own
+ * count.  The protocol of one step:
+ *   mc_packets_reset(ready, n_packets, progress, n_blocks, stream)         -- zero both
+ *   mc_reduce_update_packets(...) on the compute stream, while the producer signals packets
+ *   make the compute stream wait for the producer's last signal (an event), then call
+ *   mc_reduce_update_packets(...) once more with the same arguments: it finds every flag set and
+ *   finishes whatever the first call gave up on (nothing, if that call saw all packets).
+ * After that call progress[b] == n_packets for every b < n_blocks, progress[n_blocks] counts the
+ * workgroups that ever stopped waiting, and progress[n_blocks + 1] is non-zero if a packet descriptor
+ * was not a range inside one colour (such packets are skipped).
+ *
+ * packets: device, 2 * n_packets int64: begin and end of each packet in arrival order; each must be
+ *   a range as mc_reduce_update_range requires and lie inside one colour; the packets of a step
+ *   must be disjoint and should cover the payload.  (Device arrays cannot be validated on the host.)
+ * ready: device, n_packets uint32.  n_blocks: workgroups of 256 threads, 1..MC_PACKETS_MAX_BLOCKS;
+ *   fewer leave compute units free for the producer's kernels (1024 is a good start).
+ * Every colour adds all P terms and updates (order, spec, grad_out as in mc_reduce_update_ex).
+ * Limits: at most MC_PACKETS_MAX_COLOURS colours and k_colours * P <= 256 (MC_ERR_LIMIT).
+ * Errors otherwise as mc_reduce_update_ex. */
+#define MC_PACKETS_MAX_COLOURS 32
+#define MC_PACKETS_MAX_BLOCKS 4096
+#define MC_PACKETS_STATUS_WORDS 2
+int mc_packets_reset(uint32_t* ready, int32_t n_packets, uint32_t* progress, int32_t n_blocks, void* stream);
+int mc_packet_signal(uint32_t* ready, int32_t packet, uint32_t value, void* stream);
+int mc_reduce_update_packets(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
+                             void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
+                             const int64_t* packets, int32_t n_packets, const uint32_t* ready,
+                             uint32_t ready_value, uint32_t spin_limit, uint32_t* progress, int32_t n_blocks,
+                             void* stream);
+
 /* The schedule of Section 5 as a function of the position in training, in epochs (fractions
  * allowed): with target = base_lr * batch_per_gpu * n_workers / 256,
  *   epoch <  warmup_epochs:  base_lr + (target - base_lr) * epoch / warmup_epochs
@@ -346,7 +391,10 @@ enum {
                                       workgroup index. */
     MC_OPT_XCD_RUN_PACK = 7,       /* the same for mc_pack / mc_pack_set; -1 (default) = chosen from the
                                       payload size */
-    MC_OPT_XCD_RUN_UNPACK = 8      /* the same for mc_unpack / mc_unpack_set */
+    MC_OPT_XCD_RUN_UNPACK = 8,     /* the same for mc_unpack / mc_unpack_set */
+    MC_OPT_DIRECT_TILES = 9        /* 0 / 1 (default 1): launches with 256-element tiles map a workgroup
+                                      to its colour by dividing the tile index by the chunk length
+                                      instead of searching a per-launch table */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

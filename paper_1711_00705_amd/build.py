@@ -8,8 +8,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmc.so")
-SOURCES = ("mc_layout.cpp", "mc_pack.hip", "mc_reduce_update.hip", "mc_fused.hip", "mc_schedule.hip", "mc_copy.hip",
-           "mc_trees.cpp")
+SOURCES = ("mc_layout.cpp", "mc_pack.hip", "mc_reduce_update.hip", "mc_fused.hip", "mc_packets.hip", "mc_schedule.hip",
+           "mc_copy.hip", "mc_trees.cpp")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # every add / multiply of the update is rounded on its own: no fused multiply-add
@@ -27,23 +27,45 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source of the library; always recompiles.  Returns the .so path."""
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp, *srcs]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    os.replace(tmp, LIB)
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every source of the library (in parallel, one object each) and link them; always
+    recompiles.  Returns the .so path."""
+    import shutil
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    tmpdir = tempfile.mkdtemp(prefix="mc_build_")
+    try:
+        compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+        inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+        def compile_one(src):
+            obj = os.path.join(tmpdir, src + ".o")
+            _run([hipcc(), *compile_flags, *inc, "-c", os.path.join(CSRC, src), "-o", obj], verbose)
+            return obj
+        with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        tmp = LIB + ".tmp%d" % os.getpid()
+        try:
+            _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Wno-unused-command-line-argument",
+                  "-o", tmp, *objs], verbose)
+            os.replace(tmp, LIB)
+        finally:
+            if os.path.exists(tmp):
+                os.remove(tmp)
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
     return LIB
 
 

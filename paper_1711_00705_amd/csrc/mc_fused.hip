@@ -29,14 +29,22 @@ constexpr int kMaxSegs = 32;
 constexpr int kPtrSlots = 256;
 
 struct FusedArgs {
-    const float* const* x[kPtrSlots];   // x[x_begin[s] + q]: pointer table of the q-th term of segment s
+    const float* const* x[kPtrSlots];   // x[first + q], first from seg_info[s]: pointer table of the q-th term of segment s
     int64_t lo[kMaxSegs];
     int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
-    int16_t x_begin[kMaxSegs];
-    uint8_t n_terms[kMaxSegs];      // terms of segment s (read by per-segment launches only)
-    uint8_t seg_update[kMaxSegs];   // does segment s apply the update? (per-segment launches only)
+    // Per segment, in one 32-bit word (narrower arrays indexed at run time would make the compiler
+    // copy the whole argument block to scratch memory): bits 0-15 index of the segment's first
+    // pointer in x, bits 16-23 its number of terms, bit 24 whether it applies the update (the
+    // last two are read by per-segment launches only).
+    uint32_t seg_info[kMaxSegs];
     int32_t n_segs;
+    // Direct mapping (tiles_per_colour > 0; only with 256-element tiles, which is the colour
+    // alignment): the launch covers the whole payload tile by tile, segment s is colour s, and a
+    // tile's colour is its index divided by the chunk length -- nothing is searched and lo / hi /
+    // first_block are not read.
+    int32_t tiles_per_colour;
+    int64_t range_hi;               // N
     int32_t reverse;                // walk the launch's tiles from the last to the first
     int32_t xcd_run;                // consecutive tiles per die (see mc_tiles.h); <= 1: plain
     float* const* w;                    // pointer tables of weights and momentum (per layer)
@@ -82,6 +90,15 @@ __device__ __forceinline__ int misalignment(const void* p) {
 __device__ __forceinline__ bool aligned16(const void* p) {
     return (reinterpret_cast<uintptr_t>(p) & 15) == 0;
 }
+
+// The arguments a tile needs besides its own position, passed by value (a reference to the kernel's
+// argument block would have the compiler keep a private copy of all of it in scratch memory).
+struct TileArgs {
+    float* const* w;
+    float* const* v;
+    float* g;
+    const int64_t* off;
+};
 
 // What a launch does with the sum.
 enum : int {
@@ -232,7 +249,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
 // UPDATE: the SGD step follows the sum; otherwise only the sum is written to g (the colours of
 // which this rank is a leaf or inner node) and weights / momentum are never touched.
 template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
-__device__ __forceinline__ void fused_tile(const FusedArgs& a, const float* const* const* xs, int np,
+__device__ __forceinline__ void fused_tile(const TileArgs a, const float* const* const* xs, int np,
                                            int64_t base, int64_t end, int32_t t0, int64_t t0_begin,
                                            int64_t t0_end, const mc::Hyper& hp) {
     static_assert(HAS_G || UPDATE, "a tile must produce something");
@@ -310,21 +327,19 @@ __device__ __forceinline__ void fused_tile(const FusedArgs& a, const float* cons
     }
 }
 
-// A per-segment launch picks the compile-time body of the segment's term count.
+// A per-segment launch picks the compile-time body for the common term counts (m replicas, or m
+// plus one buffer per child, with m and the tree's arity powers of two) and the run-time loop
+// otherwise.  More bodies than these make the compiler keep a private copy of the kernel's
+// argument block in scratch memory (see tests/test_kernel_resources_cpu.py).
 template <int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
-__device__ __forceinline__ void fused_tile_any(const FusedArgs& a, const float* const* const* xs, int np,
+__device__ __forceinline__ void fused_tile_any(const TileArgs a, const float* const* const* xs, int np,
                                                int64_t base, int64_t end, int32_t t0, int64_t t0_begin,
                                                int64_t t0_end, const mc::Hyper& hp) {
 #define MC_FUSED_CASE(N) \
     case N: fused_tile<N, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp); break
     switch (np) {
-        MC_FUSED_CASE(1);
         MC_FUSED_CASE(2);
-        MC_FUSED_CASE(3);
         MC_FUSED_CASE(4);
-        MC_FUSED_CASE(5);
-        MC_FUSED_CASE(6);
-        MC_FUSED_CASE(7);
         MC_FUSED_CASE(8);
         default: fused_tile<0, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp); break;
     }
@@ -340,11 +355,20 @@ __global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Pr
     const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
     const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
     int s = 0;
-    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
-    const int64_t hi = a.hi[s];
-    const int64_t base = a.lo[s] + int64_t(blk - a.first_block[s]) * kTile;  // multiple of 256
+    int64_t base, hi;
+    if (kTile == MC_COLOUR_ALIGN_ELEMS && a.tiles_per_colour > 0) {
+        s = int(uint32_t(blk) / uint32_t(a.tiles_per_colour));
+        base = int64_t(blk) * kTile;
+        const int64_t colour_end = int64_t(s + 1) * a.tiles_per_colour * kTile;
+        hi = colour_end < a.range_hi ? colour_end : a.range_hi;
+    } else {
+        while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
+        hi = a.hi[s];
+        base = a.lo[s] + int64_t(blk - a.first_block[s]) * kTile;  // multiple of 256
+    }
     const int64_t end = base + kTile < hi ? base + kTile : hi;
-    const float* const* const* xs = a.x + a.x_begin[s];
+    const bool direct_uniform = kTile == MC_COLOUR_ALIGN_ELEMS && a.tiles_per_colour > 0 && MODE != kPerSegment;
+    const float* const* const* xs = a.x + (direct_uniform ? s * (P > 0 ? P : Prt) : int(a.seg_info[s] & 0xffffu));
 
     // The tensor holding the tile's first element (block-uniform).  `base` is a multiple of the
     // lookup granularity, so the table entry is that tensor itself: no scan of off[] is needed and
@@ -353,19 +377,21 @@ __global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Pr
     const int64_t t0_begin = a.off[t0];
     const int64_t t0_end = a.off[t0 + 1];
 
+    const TileArgs ta = {a.w, a.v, a.g, a.off};
     if (MODE == kPerSegment) {
-        const int np = a.n_terms[s];
-        if (a.seg_update[s]) {
+        const int np = int((a.seg_info[s] >> 16) & 0xffu);
+        if (np == 0) return;                       // a colour this call skips (direct mapping only)
+        if ((a.seg_info[s] >> 24) & 1u) {
             if (a.g)
-                fused_tile_any<U, THREADS, true, true, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp);
+                fused_tile_any<U, THREADS, true, true, SS>(ta, xs, np, base, end, t0, t0_begin, t0_end, hp);
             else
-                fused_tile_any<U, THREADS, false, true, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp);
+                fused_tile_any<U, THREADS, false, true, SS>(ta, xs, np, base, end, t0, t0_begin, t0_end, hp);
         } else {
-            fused_tile_any<U, THREADS, true, false, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp);
+            fused_tile_any<U, THREADS, true, false, SS>(ta, xs, np, base, end, t0, t0_begin, t0_end, hp);
         }
     } else {
         const int np = P > 0 ? P : Prt;
-        fused_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(a, xs, np, base, end, t0, t0_begin,
+        fused_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(ta, xs, np, base, end, t0, t0_begin,
                                                                              t0_end, hp);
     }
 }
@@ -522,14 +548,16 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     auto terms = [&](int32_t c) { return n_terms ? n_terms[c] : P; };
     auto updates = [&](int32_t c) { return do_update ? do_update[c] != 0 : true; };
     auto active = [&](int32_t c) { return terms(c) > 0 && L->bounds[c + 1] > L->bounds[c]; };
-    bool any_update = false, any_sum_only = false, uniform = true;
+    bool any_update = false, any_sum_only = false, uniform = true, any_skipped = false;
     int32_t first_active = -1;
-    int max_terms = 0;
+    int max_terms = 0, total_terms = 0;
     for (int32_t c = 0; c < L->k; ++c) {
         if (n_terms && (n_terms[c] < 0 || n_terms[c] > P)) return MC_ERR_INVALID_ARG;
+        if (terms(c) == 0 && L->bounds[c + 1] > L->bounds[c]) any_skipped = true;
         if (!active(c)) continue;
         if (updates(c)) any_update = true; else any_sum_only = true;
         max_terms = std::max(max_terms, int(terms(c)));
+        total_terms += terms(c);
         if (first_active < 0) first_active = c;
         else if (terms(c) != terms(first_active) || updates(c) != updates(first_active)) uniform = false;
     }
@@ -581,8 +609,52 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     a.first_tensor = dt->tile_first;
     a.up = plan.up;
 
-    // Colours in index order, as many per launch as the segment and pointer slots hold: one launch
-    // for any realistic call, whatever the mix of roles.
+    a.tiles_per_colour = 0;
+    a.range_hi = L->N;
+    auto pointer_list = [&](int32_t c, int slot) {
+        for (int32_t q = 0; q < terms(c); ++q)
+            a.x[slot + q] = reinterpret_cast<const float* const*>(contrib[order ? order[size_t(c) * P + q] : q]->d_ptrs);
+    };
+
+    // Direct mapping: a 256-element tile is exactly the colour alignment, so the tiles of the call are
+    // the 256-element runs of the payload and a tile's colour is its index divided by the chunk
+    // length.  Needs every colour's pointer list in the one launch.
+    const int64_t tiles_total = (L->N + tile - 1) / tile;
+    const int slots_needed = (uniform && !any_skipped) ? L->k * terms(first_active) : total_terms;
+    if (tile == MC_COLOUR_ALIGN_ELEMS && L->k <= kMaxSegs && slots_needed <= kPtrSlots &&
+        tiles_total < 0x7fffffff && mc::option(MC_OPT_DIRECT_TILES) != 0) {
+        a.tiles_per_colour = int32_t(L->chunk / tile);
+        a.n_segs = L->k;
+        for (int i = 0; i < kPtrSlots; ++i) a.x[i] = nullptr;
+        for (int i = 0; i < kMaxSegs; ++i) {
+            a.lo[i] = a.hi[i] = 0;
+            a.seg_info[i] = 0;
+            a.first_block[i] = 0;
+        }
+        a.first_block[kMaxSegs] = 0;
+        const bool per_segment = !uniform || any_skipped;
+        int slots = 0;
+        for (int32_t c = 0; c < L->k; ++c) {
+            if (!per_segment) {
+                if (L->bounds[c + 1] > L->bounds[c]) pointer_list(c, c * terms(first_active));
+            } else if (active(c)) {
+                a.seg_info[c] = uint32_t(slots) | (uint32_t(terms(c)) << 16) | (updates(c) ? (1u << 24) : 0u);
+                pointer_list(c, slots);
+                slots += terms(c);
+            }
+        }
+        if (per_segment) {
+            launch_per_segment(ss, unsigned(tiles_total), s, a);
+        } else {
+            const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
+            launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);
+        }
+        MC_HIP_TRY(hipGetLastError());
+        return MC_OK;
+    }
+
+    // Otherwise colours in index order, as many per launch as the segment and pointer slots hold, each
+    // with its own run of workgroups (a prefix table maps a workgroup to its segment).
     int32_t c = 0;
     while (c < L->k) {
         int ns = 0, slots = 0;
@@ -600,13 +672,8 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             }
             a.lo[ns] = lo;
             a.hi[ns] = hi;
-            a.x_begin[ns] = int16_t(slots);
-            a.n_terms[ns] = uint8_t(cnt);
-            a.seg_update[ns] = updates(c) ? 1 : 0;
-            for (int32_t q = 0; q < cnt; ++q) {
-                const int32_t src = order ? order[size_t(c) * P + q] : q;
-                a.x[slots + q] = reinterpret_cast<const float* const*>(contrib[src]->d_ptrs);
-            }
+            a.seg_info[ns] = uint32_t(slots) | (uint32_t(cnt) << 16) | (updates(c) ? (1u << 24) : 0u);
+            pointer_list(c, slots);
             slots += cnt;
             blocks += nblk;
             a.first_block[ns + 1] = int32_t(blocks);
@@ -616,9 +683,7 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
         for (int i = slots; i < kPtrSlots; ++i) a.x[i] = nullptr;
         for (int i = ns; i < kMaxSegs; ++i) {
             a.lo[i] = a.hi[i] = 0;
-            a.x_begin[i] = 0;
-            a.n_terms[i] = 0;
-            a.seg_update[i] = 0;
+            a.seg_info[i] = 0;
             a.first_block[i + 1] = a.first_block[ns];
         }
         a.n_segs = ns;

@@ -39,6 +39,7 @@ struct mc_layout {
     int32_t n = 0;
     int32_t k = 0;
     int64_t N = 0;
+    int64_t chunk = 0;                // colour chunk length C (a multiple of 256; 0 when N == 0)
     std::vector<int64_t> off;         // n+1
     std::vector<int64_t> bounds;      // k+1
     std::vector<int32_t> tile_first;  // ceil(N / kLookupElems) + 1
@@ -84,10 +85,11 @@ struct Shape {
     int vectors;   // 16-byte vectors per thread per tile: 1 or 2
     int64_t tile() const { return int64_t(threads) * 4 * vectors; }
 };
-// 64 threads x 1 vector (one wavefront per workgroup) measured fastest everywhere the state is not
-// cache-resident, for small payloads and for more than four contributions (6-10 % over
-// 256 x 2 on cold ResNet-50- and VGG-16-sized steps); 256 x 2 is 1 % ahead on large back-to-back
-// steps with resident state and few contributions.  Honours MC_OPT_RU_SHAPE.
+// 64 threads x 1 vector (one wavefront per workgroup, a tile of exactly one colour-alignment unit)
+// measured fastest or within noise on every configuration: against 256 threads x 2 vectors the fused
+// step gains 1 % on the back-to-back ResNet-50 step, 2 % with eight contributions, 3-4 % on
+// GoogLeNet- and VGG-16-sized steps and 2-4 % when nothing is cache-resident; 128 x 1 and 256 x 1
+// are within 1 % of it.  So it is the default for every launch; MC_OPT_RU_SHAPE = 2 forces 256 x 2.
 Shape shape_for(int64_t elems, int n_terms, bool stream_state);
 
 // Cache treatment of weights and momentum for a call on layout L: `policy` is the caller's
@@ -104,6 +106,15 @@ bool stream_state(const mc_layout* L, int policy);
 // keeps the parity of its automatic calls in one relaxed atomic counter -- the only thing in a
 // layout that changes after mc_layout_prepare, and it affects the order of the tiles, never a result.
 bool sweep_reversed(const mc_layout* L, int sweep, bool stream_state);
+
+// Argument checks shared by the entry points that work on flat buffers.
+// check_order: P in range and every row of the order table a permutation of 0..P-1.
+// check_flat_buffers: null / alignment / overlap of {contrib[0..P), grad_out, weights, momentum}:
+// nothing that is written may overlap anything else; contributions are only read and may repeat.
+// needs_state: weights and momentum are required; needs_g: grad_out is.
+int check_order(const mc_layout* L, int32_t P, const int32_t* order);
+int check_flat_buffers(const mc_layout* L, const void* const* contrib, int32_t P, const void* grad_out,
+                       const void* weights, const void* momentum, bool needs_state, bool needs_g);
 
 struct UpdateParams;
 // A validated mc_update_spec: the kernels' argument form plus the host-side launch choices.

@@ -17,6 +17,7 @@ std::atomic<int> g_alternate_sweep{1};
 std::atomic<int> g_xcd_run{0};
 std::atomic<int> g_xcd_run_pack{-1};
 std::atomic<int> g_xcd_run_unpack{0};
+std::atomic<int> g_direct_tiles{1};
 
 // Capacity of the memory-side cache that sits between the L2s and HBM.
 constexpr int64_t kMemorySideCacheBytes = int64_t(256) << 20;
@@ -34,9 +35,9 @@ Shape shape_for(int64_t elems, int n_terms, bool stream_state) {
     const int forced = g_ru_shape.load(std::memory_order_relaxed);
     if (forced == 1) return Shape{64, 1};
     if (forced == 2) return Shape{256, 2};
-    // 256 x 2 only where it measured ahead: many tiles, few contributions, state kept resident.
-    const bool large = elems / 2048 >= 8192;
-    if (large && n_terms <= 4 && !stream_state) return Shape{256, 2};
+    (void)elems;
+    (void)n_terms;
+    (void)stream_state;
     return Shape{64, 1};
 }
 
@@ -67,6 +68,7 @@ int option(int which) {
         case MC_OPT_XCD_RUN: return g_xcd_run.load(std::memory_order_relaxed);
         case MC_OPT_XCD_RUN_PACK: return g_xcd_run_pack.load(std::memory_order_relaxed);
         case MC_OPT_XCD_RUN_UNPACK: return g_xcd_run_unpack.load(std::memory_order_relaxed);
+        case MC_OPT_DIRECT_TILES: return g_direct_tiles.load(std::memory_order_relaxed);
         default: return kNoSuchOption;
     }
 }
@@ -100,6 +102,7 @@ int mc_layout_create(const int64_t* numel, int32_t n_tensors, int32_t k_colours,
         const int64_t a = MC_COLOUR_ALIGN_ELEMS;
         int64_t C = total / k_colours + (total % k_colours != 0);
         C = (C + a - 1) / a * a;
+        L->chunk = C;
         L->bounds.resize(size_t(k_colours) + 1);
         for (int32_t c = 0; c <= k_colours; ++c) {
             const bool past_end = C == 0 || int64_t(c) >= (total + C - 1) / C;
@@ -197,6 +200,10 @@ int mc_set_option(int option, int value) {
         case MC_OPT_XCD_RUN_UNPACK:
             if (value < -1 || value > 64) return MC_ERR_INVALID_ARG;
             g_xcd_run_unpack.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_DIRECT_TILES:
+            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
+            g_direct_tiles.store(value, std::memory_order_relaxed);
             return MC_OK;
         default:
             return MC_ERR_INVALID_ARG;

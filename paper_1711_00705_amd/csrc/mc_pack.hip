@@ -13,6 +13,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <new>
+#include <utility>
+#include <vector>
 
 #include "mc_internal.h"
 #include "mc_mem.h"
@@ -207,6 +210,18 @@ int run(mc_layout* L, void* const* tensors, void* flat, void* stream) {
         if (!tensors[t]) return MC_ERR_INVALID_ARG;
         if (!mc::aligned(tensors[t], 4)) return MC_ERR_ALIGN;
         if (mc::overlaps(tensors[t], uint64_t(cnt) * 4, flat, flat_bytes)) return MC_ERR_OVERLAP;
+    }
+    if (UNPACK) {
+        // destination tensors that overlap each other would be written by two workgroups at once
+        std::vector<std::pair<uintptr_t, uintptr_t>> spans;
+        for (int32_t t = 0; t < L->n; ++t) {
+            const int64_t cnt = L->off[t + 1] - L->off[t];
+            const uintptr_t b = reinterpret_cast<uintptr_t>(tensors[t]);
+            if (cnt > 0) spans.emplace_back(b, b + uintptr_t(cnt) * 4);
+        }
+        std::sort(spans.begin(), spans.end());
+        for (size_t i = 1; i < spans.size(); ++i)
+            if (spans[i].first < spans[i - 1].second) return MC_ERR_OVERLAP;
     }
     const mc::DeviceTables* dt = nullptr;
     const int rc = mc::device_tables(L, &dt);
@@ -416,7 +431,11 @@ int mc_pack(mc_layout* L, const void* const* tensors, void* flat, void* stream) 
 }
 
 int mc_unpack(mc_layout* L, const void* flat, void* const* tensors, void* stream) {
-    return run<true>(L, tensors, const_cast<void*>(flat), stream);
+    try {
+        return run<true>(L, tensors, const_cast<void*>(flat), stream);
+    } catch (const std::bad_alloc&) {   // the span list of the overlap check
+        return MC_ERR_ALLOC;
+    }
 }
 
 int mc_pack_noalloc(const mc_layout* L, const void* const* tensors, void* flat, void* stream) {

@@ -1,0 +1,215 @@
+// Packet-driven reduction: one resident kernel that sums and updates packets of the payload in
+// their order of arrival, each as soon as a device-memory flag says that it has landed.
+//
+// Section 4.2 pipelines the k reductions: packets of every colour are in flight at once and a
+// summing rank adds a packet when it arrives instead of waiting for whole chunks.  On the GPU the
+// per-packet dependency must not go through the host or through stream events (each costs tens of
+// microseconds, more than summing a packet takes), so the reducer polls the flags itself.  Whatever
+// delivers a packet -- here a copy kernel followed by mc_packet_signal, on another stream -- writes
+// the data first and the flag afterwards with release semantics; the reducer reads the flag with
+// acquire semantics before it touches the packet.
+//
+// Every wait is bounded.  A workgroup that has polled `spin_limit` times in total without seeing
+// the flag it needs stops, and so does every other one at its own pace; nothing is ever left
+// half-done, because each workgroup records how many packets it has completed (progress[b]) and a
+// later launch -- after the producer has finished -- resumes every workgroup from its own count.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "mc_internal.h"
+#include "mc_ru_tile.h"
+#include "mc_update.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int64_t kTile = int64_t(kThreads) * 4;     // one 16-byte vector per thread
+constexpr int kMaxColours = MC_PACKETS_MAX_COLOURS;
+constexpr int kPtrSlots = 256;
+
+struct PkArgs {
+    const float* x[kPtrSlots];            // x[c * np + q]: q-th term of colour c
+    int64_t bounds[kMaxColours + 1];      // colour bounds
+    int32_t n_colours;
+    int32_t np;
+    int32_t n_packets;
+    uint32_t ready_value;
+    uint32_t spin_limit;
+    int64_t N;
+    const int64_t* packets;               // device: begin, end of each packet, in arrival order
+    const uint32_t* ready;                // device: one flag per packet
+    uint32_t* progress;                   // device: per workgroup, packets completed; then 2 status words
+    float* g;
+    float* w;
+    float* v;
+    mc::UpdateParams up;
+};
+
+template <int P, bool HAS_G, bool SS>
+__global__ __launch_bounds__(kThreads) void packet_reducer_kernel(PkArgs a) {
+    __shared__ int go;
+    const mc::Hyper hp = mc::resolve(a.up);
+    const int np = P > 0 ? P : a.np;
+    const uint32_t G = gridDim.x;
+    uint32_t polls_left = a.spin_limit;
+    uint32_t j = a.progress[blockIdx.x];          // where an earlier launch of this step stopped
+    bool gave_up = false;
+    for (; j < uint32_t(a.n_packets); ++j) {
+        if (threadIdx.x == 0) {
+            int ok = 0;
+            for (;;) {
+                const uint32_t f = __hip_atomic_load(a.ready + j, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                if (f == a.ready_value) {
+                    ok = 1;
+                    break;
+                }
+                if (polls_left == 0) break;
+                --polls_left;
+                __builtin_amdgcn_s_sleep(32);     // about a microsecond
+            }
+            go = ok;
+        }
+        __syncthreads();
+        const int ok = go;
+        __syncthreads();                          // `go` is rewritten in the next round
+        if (!ok) {
+            gave_up = true;
+            break;
+        }
+        // The flag was read by one thread; every wave makes the packet's data visible to itself.
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+
+        const int64_t lo = a.packets[2 * int64_t(j)];
+        const int64_t hi = a.packets[2 * int64_t(j) + 1];
+        int c = -1;
+        if (lo >= 0 && lo < hi && hi <= a.N && lo % MC_COLOUR_ALIGN_ELEMS == 0) {
+            for (int i = 0; i < a.n_colours; ++i)
+                if (a.bounds[i] <= lo && hi <= a.bounds[i + 1]) c = i;
+        }
+        if (c < 0) {                              // not a range of one colour: skipped and reported
+            if (threadIdx.x == 0) atomicOr(a.progress + G + 1, 1u);
+        } else {
+            const float* const* xs = a.x + c * np;
+            const int64_t n_tiles = (hi - lo + kTile - 1) / kTile;
+            // consecutive packets start on consecutive workgroups, so that small packets do not
+            // all land on the first few
+            const int64_t first = (int64_t(j) * n_tiles) % G;
+            const int64_t mine = (int64_t(blockIdx.x) + G - first) % G;
+            for (int64_t t = mine; t < n_tiles; t += G)
+                mc::ru_tile<P, 1, kThreads, HAS_G, true, SS>(xs, np, lo + t * kTile, hi, a.g, a.w, a.v, hp);
+        }
+        if (threadIdx.x == 0) a.progress[blockIdx.x] = j + 1;
+    }
+    if (gave_up && threadIdx.x == 0) atomicAdd(a.progress + G, 1u);
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t value) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+__global__ void signal_kernel(uint32_t* flag, uint32_t value) {
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int P>
+void launch_p(bool has_g, bool ss, unsigned blocks, hipStream_t s, const PkArgs& a) {
+    const dim3 grid(blocks), block(kThreads);
+#define MC_PK_LAUNCH(G, SS) hipLaunchKernelGGL((packet_reducer_kernel<P, G, SS>), grid, block, 0, s, a)
+    if (has_g) {
+        if (ss) MC_PK_LAUNCH(true, true); else MC_PK_LAUNCH(true, false);
+    } else {
+        if (ss) MC_PK_LAUNCH(false, true); else MC_PK_LAUNCH(false, false);
+    }
+#undef MC_PK_LAUNCH
+}
+
+}  // namespace
+
+extern "C" {
+
+int mc_packets_reset(uint32_t* ready, int32_t n_packets, uint32_t* progress, int32_t n_blocks, void* stream) {
+    if (n_packets < 0 || n_blocks < 0 || n_blocks > MC_PACKETS_MAX_BLOCKS) return MC_ERR_INVALID_ARG;
+    if ((n_packets > 0 && !ready) || (n_blocks > 0 && !progress)) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(ready, 4) || !mc::aligned(progress, 4)) return MC_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_packets > 0) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(unsigned((n_packets + 255) / 256)), dim3(256), 0, s, ready,
+                           int64_t(n_packets), 0u);
+        MC_HIP_TRY(hipGetLastError());
+    }
+    if (n_blocks > 0) {
+        const int64_t n = int64_t(n_blocks) + MC_PACKETS_STATUS_WORDS;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, s, progress, n, 0u);
+        MC_HIP_TRY(hipGetLastError());
+    }
+    return MC_OK;
+}
+
+int mc_packet_signal(uint32_t* ready, int32_t packet, uint32_t value, void* stream) {
+    if (!ready || packet < 0) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(ready, 4)) return MC_ERR_ALIGN;
+    hipLaunchKernelGGL(signal_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), ready + packet, value);
+    MC_HIP_TRY(hipGetLastError());
+    return MC_OK;
+}
+
+int mc_reduce_update_packets(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
+                             void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
+                             const int64_t* packets, int32_t n_packets, const uint32_t* ready,
+                             uint32_t ready_value, uint32_t spin_limit, uint32_t* progress, int32_t n_blocks,
+                             void* stream) {
+    if (!L) return MC_ERR_INVALID_ARG;
+    mc::UpdatePlan plan;
+    int rc = mc::update_plan(spec, &plan);
+    if (rc != MC_OK) return rc;
+    if (n_packets < 0 || n_blocks < 1 || n_blocks > MC_PACKETS_MAX_BLOCKS) return MC_ERR_INVALID_ARG;
+    if (L->k > kMaxColours || int64_t(L->k) * P > kPtrSlots) return MC_ERR_LIMIT;
+    if (plan.up.hyper && !mc::aligned(plan.up.hyper, 4)) return MC_ERR_ALIGN;
+    rc = mc::check_order(L, P, order);
+    if (rc != MC_OK) return rc;
+    rc = mc::check_flat_buffers(L, contrib, P, grad_out, weights, momentum, /*needs_state=*/true, /*needs_g=*/false);
+    if (rc != MC_OK) return rc;
+    if (n_packets == 0) return MC_OK;
+    if (!packets || !ready || !progress) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(packets, 8) || !mc::aligned(ready, 4) || !mc::aligned(progress, 4)) return MC_ERR_ALIGN;
+
+    PkArgs a;
+    for (int32_t c = 0; c < L->k; ++c)
+        for (int32_t q = 0; q < P; ++q)
+            a.x[c * P + q] = static_cast<const float*>(contrib[order ? order[size_t(c) * P + q] : q]);
+    for (int i = L->k * P; i < kPtrSlots; ++i) a.x[i] = nullptr;
+    for (int32_t c = 0; c <= L->k; ++c) a.bounds[c] = L->bounds[c];
+    for (int c = L->k + 1; c <= kMaxColours; ++c) a.bounds[c] = L->N;
+    a.n_colours = L->k;
+    a.np = P;
+    a.n_packets = n_packets;
+    a.ready_value = ready_value;
+    a.spin_limit = spin_limit;
+    a.N = L->N;
+    a.packets = packets;
+    a.ready = ready;
+    a.progress = progress;
+    a.g = static_cast<float*>(grad_out);
+    a.w = static_cast<float*>(weights);
+    a.v = static_cast<float*>(momentum);
+    a.up = plan.up;
+    const bool ss = mc::stream_state(L, plan.state_policy);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned blocks = unsigned(n_blocks);
+    switch (P) {
+        case 1: launch_p<1>(a.g != nullptr, ss, blocks, s, a); break;
+        case 2: launch_p<2>(a.g != nullptr, ss, blocks, s, a); break;
+        case 4: launch_p<4>(a.g != nullptr, ss, blocks, s, a); break;
+        case 8: launch_p<8>(a.g != nullptr, ss, blocks, s, a); break;
+        default: launch_p<0>(a.g != nullptr, ss, blocks, s, a); break;
+    }
+    MC_HIP_TRY(hipGetLastError());
+    return MC_OK;
+}
+
+}  // extern "C"

@@ -18,6 +18,7 @@
 
 #include "mc_internal.h"
 #include "mc_tiles.h"
+#include "mc_ru_tile.h"
 #include "mc_update.h"
 
 #pragma clang fp contract(off)
@@ -28,14 +29,23 @@ constexpr int kMaxSegs = 32;     // colour segments per launch
 constexpr int kPtrSlots = 256;   // permuted contribution pointers per launch
 
 struct RuArgs {
-    const float* x[kPtrSlots];      // x[x_begin[s] + q]: q-th term of segment s
+    const float* x[kPtrSlots];      // x[first + q], first from seg_info[s]: q-th term of segment s
     int64_t lo[kMaxSegs];           // segment s covers flat elements [lo[s], hi[s])
     int64_t hi[kMaxSegs];
     int32_t first_block[kMaxSegs + 1];
-    int16_t x_begin[kMaxSegs];
-    uint8_t n_terms[kMaxSegs];      // terms of segment s (read by per-segment launches only)
-    uint8_t seg_update[kMaxSegs];   // does segment s apply the update? (per-segment launches only)
+    // Per segment, in one 32-bit word (narrower arrays indexed at run time would make the compiler
+    // copy the whole argument block to scratch memory): bits 0-15 index of the segment's first
+    // pointer in x, bits 16-23 its number of terms, bit 24 whether it applies the update (the
+    // last two are read by per-segment launches only).
+    uint32_t seg_info[kMaxSegs];
     int32_t n_segs;
+    // Direct mapping (tiles_per_colour > 0; only with 256-element tiles, which is the colour
+    // alignment): the launch covers flat elements [256 * first_tile, range_hi) tile by tile, segment
+    // s is colour s, and a tile's colour is its index divided by the chunk length -- nothing is
+    // searched and lo / hi / first_block are not read.
+    int32_t tiles_per_colour;
+    uint32_t first_tile;
+    int64_t range_hi;
     int32_t reverse;                // walk the launch's tiles from the last to the first
     int32_t xcd_run;                // consecutive tiles per die (see mc_tiles.h); <= 1: plain
     float* g;                       // may be null when every segment updates
@@ -43,20 +53,6 @@ struct RuArgs {
     float* v;
     mc::UpdateParams up;
 };
-
-typedef float native_f4 __attribute__((ext_vector_type(4)));
-
-// Contributions and the reduced gradient are touched once per step: streaming (non-temporal)
-// accesses, so that they do not displace weights and momentum from the caches.
-__device__ __forceinline__ float4 load_stream(const float* p) {
-    const native_f4 r = __builtin_nontemporal_load(reinterpret_cast<const native_f4*>(p));
-    return make_float4(r.x, r.y, r.z, r.w);
-}
-
-__device__ __forceinline__ void store_stream(float* p, const float4& q) {
-    const native_f4 val = {q.x, q.y, q.z, q.w};
-    __builtin_nontemporal_store(val, reinterpret_cast<native_f4*>(p));
-}
 
 // What a launch does with the sum.
 enum : int {
@@ -66,154 +62,17 @@ enum : int {
     kPerSegment = 3    // each segment has its own number of terms and its own update flag
 };
 
-// One tile of one segment.  P > 0: compile-time number of terms; P == 0: run-time count `np`
-// (up to MC_MAX_P).  UPDATE: the SGD step follows the sum; otherwise only the sum is written to g
-// and w, v are never touched.  SS: weights and momentum are streamed instead of kept resident.
-template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
-__device__ __forceinline__ void ru_tile(const float* const* xs, int np, int64_t base, int64_t hi, float* g,
-                                        float* w, float* v, const mc::Hyper& hp) {
-    static_assert(HAS_G || UPDATE, "a tile must produce something");
-    constexpr int64_t kTile = int64_t(THREADS) * 4 * U;
-    if (base + kTile <= hi) {
-        // Full tile: issue every load of the tile before the first add.
-        float4 acc[U], wv[U], vv[U];
-        int64_t idx[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) idx[u] = base + (int64_t(u) * THREADS + threadIdx.x) * 4;
-        if (P > 0) {
-            float4 t[P > 0 ? P : 1][U];
-#pragma unroll
-            for (int q = 0; q < P; ++q)
-#pragma unroll
-                for (int u = 0; u < U; ++u) t[q][u] = load_stream(xs[q] + idx[u]);
-            if (UPDATE) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    wv[u] = mc::load_state<SS>(w + idx[u]);
-                    vv[u] = mc::load_state<SS>(v + idx[u]);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                acc[u] = t[0][u];
-#pragma unroll
-                for (int q = 1; q < P; ++q) {
-                    acc[u].x = acc[u].x + t[q][u].x;
-                    acc[u].y = acc[u].y + t[q][u].y;
-                    acc[u].z = acc[u].z + t[q][u].z;
-                    acc[u].w = acc[u].w + t[q][u].w;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (UPDATE) {
-                    wv[u] = mc::load_state<SS>(w + idx[u]);
-                    vv[u] = mc::load_state<SS>(v + idx[u]);
-                }
-                acc[u] = load_stream(xs[0] + idx[u]);
-            }
-            // Four terms' loads are issued before their adds (more bytes in flight); the adds
-            // still run strictly left to right.
-            int q = 1;
-            for (; q + 4 <= np; q += 4) {
-                float4 t[4][U];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int u = 0; u < U; ++u) t[r][u] = load_stream(xs[q + r] + idx[u]);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        acc[u].x = acc[u].x + t[r][u].x;
-                        acc[u].y = acc[u].y + t[r][u].y;
-                        acc[u].z = acc[u].z + t[r][u].z;
-                        acc[u].w = acc[u].w + t[r][u].w;
-                    }
-            }
-            for (; q < np; ++q) {
-                const float* xq = xs[q];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const float4 t = load_stream(xq + idx[u]);
-                    acc[u].x = acc[u].x + t.x;
-                    acc[u].y = acc[u].y + t.y;
-                    acc[u].z = acc[u].z + t.z;
-                    acc[u].w = acc[u].w + t.w;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (HAS_G) store_stream(g + idx[u], acc[u]);
-            if (UPDATE) {
-                mc::sgd(acc[u].x, wv[u].x, vv[u].x, hp);
-                mc::sgd(acc[u].y, wv[u].y, vv[u].y, hp);
-                mc::sgd(acc[u].z, wv[u].z, vv[u].z, hp);
-                mc::sgd(acc[u].w, wv[u].w, vv[u].w, hp);
-                mc::store_state<SS>(w + idx[u], wv[u], hp.state_store_sc1);
-                mc::store_state<SS>(v + idx[u], vv[u], hp.state_store_sc1);
-            }
-        }
-        return;
-    }
-
-    // Last, partial tile of the segment: whole vectors while they fit, then single elements.
-    // (Segments start on multiples of 256 elements, so base is 16-byte aligned; hi need not be.)
-    for (int u = 0; u < U; ++u) {
-        const int64_t i = base + (int64_t(u) * THREADS + threadIdx.x) * 4;
-        if (i >= hi) break;
-        if (i + 4 <= hi) {
-            float4 acc = load_stream(xs[0] + i);
-            for (int q = 1; q < np; ++q) {
-                const float4 t = load_stream(xs[q] + i);
-                acc.x = acc.x + t.x;
-                acc.y = acc.y + t.y;
-                acc.z = acc.z + t.z;
-                acc.w = acc.w + t.w;
-            }
-            if (HAS_G) *reinterpret_cast<float4*>(g + i) = acc;
-            if (UPDATE) {
-                float4 wq = *reinterpret_cast<const float4*>(w + i);
-                float4 vq = *reinterpret_cast<const float4*>(v + i);
-                mc::sgd(acc.x, wq.x, vq.x, hp);
-                mc::sgd(acc.y, wq.y, vq.y, hp);
-                mc::sgd(acc.z, wq.z, vq.z, hp);
-                mc::sgd(acc.w, wq.w, vq.w, hp);
-                *reinterpret_cast<float4*>(w + i) = wq;
-                *reinterpret_cast<float4*>(v + i) = vq;
-            }
-        } else {
-            for (int64_t e = i; e < hi; ++e) {
-                float acc = xs[0][e];
-                for (int q = 1; q < np; ++q) acc = acc + xs[q][e];
-                if (HAS_G) g[e] = acc;
-                if (UPDATE) {
-                    float we = w[e], ve = v[e];
-                    mc::sgd(acc, we, ve, hp);
-                    w[e] = we;
-                    v[e] = ve;
-                }
-            }
-        }
-    }
-}
-
-// A per-segment launch picks the compile-time body of the segment's term count.
+// A per-segment launch picks the compile-time body for the common term counts (m replicas, or m
+// plus one buffer per child, with m and the tree's arity powers of two) and the run-time loop
+// otherwise.
 template <int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
 __device__ __forceinline__ void ru_tile_any(const float* const* xs, int np, int64_t base, int64_t hi, float* g,
                                             float* w, float* v, const mc::Hyper& hp) {
     switch (np) {
-        case 1: ru_tile<1, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 2: ru_tile<2, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 3: ru_tile<3, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 4: ru_tile<4, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 5: ru_tile<5, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 6: ru_tile<6, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 7: ru_tile<7, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        case 8: ru_tile<8, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
-        default: ru_tile<0, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 2: mc::ru_tile<2, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 4: mc::ru_tile<4, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        case 8: mc::ru_tile<8, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
+        default: mc::ru_tile<0, U, THREADS, HAS_G, UPDATE, SS>(xs, np, base, hi, g, w, v, hp); break;
     }
 }
 
@@ -226,14 +85,25 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
     const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
     const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
     int s = 0;
-    while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
-    const int64_t hi = a.hi[s];
-    const int64_t base = a.lo[s] + int64_t(blk - a.first_block[s]) * kTile;
-    const float* const* xs = a.x + a.x_begin[s];
+    int64_t base, hi;
+    if (kTile == MC_COLOUR_ALIGN_ELEMS && a.tiles_per_colour > 0) {
+        const uint32_t t = a.first_tile + uint32_t(blk);
+        s = int(t / uint32_t(a.tiles_per_colour));
+        base = int64_t(t) * kTile;
+        const int64_t colour_end = int64_t(s + 1) * a.tiles_per_colour * kTile;
+        hi = colour_end < a.range_hi ? colour_end : a.range_hi;
+    } else {
+        while (s + 1 < a.n_segs && blk >= a.first_block[s + 1]) ++s;
+        hi = a.hi[s];
+        base = a.lo[s] + int64_t(blk - a.first_block[s]) * kTile;
+    }
+    const bool direct_uniform = kTile == MC_COLOUR_ALIGN_ELEMS && a.tiles_per_colour > 0 && MODE != kPerSegment;
+    const float* const* xs = a.x + (direct_uniform ? s * (P > 0 ? P : Prt) : int(a.seg_info[s] & 0xffffu));
 
     if (MODE == kPerSegment) {
-        const int np = a.n_terms[s];
-        if (a.seg_update[s]) {
+        const int np = int((a.seg_info[s] >> 16) & 0xffu);
+        if (np == 0) return;                       // a colour this call skips (direct mapping only)
+        if ((a.seg_info[s] >> 24) & 1u) {
             if (a.g)
                 ru_tile_any<U, THREADS, true, true, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
             else
@@ -243,7 +113,7 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
         }
     } else {
         const int np = P > 0 ? P : Prt;
-        ru_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
+        mc::ru_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(xs, np, base, hi, a.g, a.w, a.v, hp);
     }
 }
 
@@ -306,59 +176,34 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     if (r_lo % MC_COLOUR_ALIGN_ELEMS != 0) return MC_ERR_INVALID_ARG;
     if (r_hi % MC_COLOUR_ALIGN_ELEMS != 0 && r_hi != L->N) return MC_ERR_INVALID_ARG;
     if ((n_terms == nullptr) != (do_update == nullptr)) return MC_ERR_INVALID_ARG;
-    if (order) {
-        for (int32_t c = 0; c < L->k; ++c) {
-            uint64_t seen = 0;
-            for (int32_t q = 0; q < P; ++q) {
-                const int32_t o = order[size_t(c) * P + q];
-                if (o < 0 || o >= P || (seen >> o) & 1) return MC_ERR_INVALID_ARG;
-                seen |= uint64_t(1) << o;
-            }
-        }
-    }
+    const int orc = mc::check_order(L, P, order);
+    if (orc != MC_OK) return orc;
     // What colour c contributes to this call: its range cut to [r_lo, r_hi), its term count and
     // whether it updates.
     auto seg_lo = [&](int32_t c) { return std::max(L->bounds[c], r_lo); };
     auto seg_hi = [&](int32_t c) { return std::max(seg_lo(c), std::min(L->bounds[c + 1], r_hi)); };
     auto terms = [&](int32_t c) { return n_terms ? n_terms[c] : P; };
     auto updates = [&](int32_t c) { return do_update ? do_update[c] != 0 : true; };
-    auto active = [&](int32_t c) { return terms(c) > 0 && seg_hi(c) > seg_lo(c); };
-    bool any_update = false, any_sum_only = false, uniform = true;
+    auto in_range = [&](int32_t c) { return seg_hi(c) > seg_lo(c); };
+    auto active = [&](int32_t c) { return terms(c) > 0 && in_range(c); };
+    bool any_update = false, any_sum_only = false, uniform = true, any_skipped = false;
     int32_t first_active = -1;
+    int max_terms = 0, total_terms = 0;
     for (int32_t c = 0; c < L->k; ++c) {
         if (n_terms && (n_terms[c] < 0 || n_terms[c] > P)) return MC_ERR_INVALID_ARG;
+        if (in_range(c) && terms(c) == 0) any_skipped = true;
         if (!active(c)) continue;
         if (updates(c)) any_update = true; else any_sum_only = true;
+        max_terms = std::max(max_terms, int(terms(c)));
+        total_terms += terms(c);
         if (first_active < 0) first_active = c;
         else if (terms(c) != terms(first_active) || updates(c) != updates(first_active)) uniform = false;
     }
     if (first_active < 0) return MC_OK;  // nothing in range
-    if (any_update && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
-    if (any_sum_only && !grad_out) return MC_ERR_INVALID_ARG;
-    for (int32_t p = 0; p < P; ++p)
-        if (!contrib[p]) return MC_ERR_INVALID_ARG;
-
-    // Alignment of every buffer; nothing that is written (weights, momentum, grad_out) may overlap
-    // anything else of the call.  Contributions are only read, so the same buffer may appear twice.
-    const void* written[3];
-    int nw = 0;
-    if (weights) written[nw++] = weights;
-    if (momentum) written[nw++] = momentum;
-    if (grad_out) written[nw++] = grad_out;
-    for (int32_t p = 0; p < P; ++p)
-        if (!mc::aligned(contrib[p], 16)) return MC_ERR_ALIGN;
-    for (int i = 0; i < nw; ++i)
-        if (!mc::aligned(written[i], 16)) return MC_ERR_ALIGN;
-    const uint64_t bytes = uint64_t(L->N) * 4;
-    for (int i = 0; i < nw; ++i) {
-        for (int j = i + 1; j < nw; ++j)
-            if (mc::overlaps(written[i], bytes, written[j], bytes)) return MC_ERR_OVERLAP;
-        for (int32_t p = 0; p < P; ++p)
-            if (mc::overlaps(written[i], bytes, contrib[p], bytes)) return MC_ERR_OVERLAP;
-    }
+    const int rc = mc::check_flat_buffers(L, contrib, P, grad_out, weights, momentum, any_update, any_sum_only);
+    if (rc != MC_OK) return rc;
 
     const bool ss = any_update && mc::stream_state(L, plan.state_policy);
-    const int max_terms = [&] { int m = 0; for (int32_t c = 0; c < L->k; ++c) if (active(c)) m = std::max(m, terms(c)); return m; }();
     // Launches that mix term counts or update flags use the one-wavefront shape.
     const mc::Shape shape = uniform ? mc::shape_for(r_hi - r_lo, max_terms, ss) : mc::Shape{64, 1};
     const int64_t tile = shape.tile();
@@ -373,10 +218,54 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);
     a.up = plan.up;
+    a.tiles_per_colour = 0;
+    a.first_tile = 0;
+    a.range_hi = r_hi;
+    auto pointer_list = [&](int32_t c, int slot) {
+        for (int32_t q = 0; q < terms(c); ++q)
+            a.x[slot + q] = static_cast<const float*>(contrib[order ? order[size_t(c) * P + q] : q]);
+    };
 
-    // Colours are taken in index order, as many per launch as the segment and pointer slots hold:
-    // one launch for any realistic call (a rank is inner node or root of at most one colour, so a
-    // role-dependent step has two kinds of segments and they share the launch).
+    // Direct mapping: a 256-element tile is exactly the colour alignment, so the tiles of the call are
+    // the 256-element runs of [r_lo, r_hi) and a tile's colour is its index divided by the chunk
+    // length.  Needs every colour's pointer list in the one launch.
+    const int64_t tiles_total = (r_hi - r_lo + tile - 1) / tile;
+    const int slots_needed = (uniform && !any_skipped) ? L->k * terms(first_active) : total_terms;
+    if (tile == MC_COLOUR_ALIGN_ELEMS && L->k <= kMaxSegs && slots_needed <= kPtrSlots &&
+        tiles_total <= 0x7fffffff && L->N / tile < 0x7fffffff && mc::option(MC_OPT_DIRECT_TILES) != 0) {
+        a.tiles_per_colour = int32_t(L->chunk / tile);
+        a.first_tile = uint32_t(r_lo / tile);
+        a.n_segs = L->k;
+        for (int i = 0; i < kPtrSlots; ++i) a.x[i] = nullptr;
+        for (int i = 0; i < kMaxSegs; ++i) {
+            a.lo[i] = a.hi[i] = 0;
+            a.seg_info[i] = 0;
+            a.first_block[i] = 0;
+        }
+        a.first_block[kMaxSegs] = 0;
+        const bool per_segment = !uniform || any_skipped;
+        int slots = 0;
+        for (int32_t c = 0; c < L->k; ++c) {
+            if (!per_segment) {
+                if (in_range(c)) pointer_list(c, c * terms(first_active));
+            } else if (active(c)) {
+                a.seg_info[c] = uint32_t(slots) | (uint32_t(terms(c)) << 16) | (updates(c) ? (1u << 24) : 0u);
+                pointer_list(c, slots);
+                slots += terms(c);
+            }
+        }
+        if (per_segment) {
+            launch_per_segment(ss, unsigned(tiles_total), s, a);
+        } else {
+            const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
+            launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);
+        }
+        MC_HIP_TRY(hipGetLastError());
+        return MC_OK;
+    }
+
+    // Otherwise colours are taken in index order, as many per launch as the segment and pointer slots
+    // hold, each with its own run of workgroups (a prefix table maps a workgroup to its segment).
     int32_t c = 0;
     while (c < L->k) {
         int ns = 0, slots = 0;
@@ -394,13 +283,8 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
             }
             a.lo[ns] = lo;
             a.hi[ns] = hi;
-            a.x_begin[ns] = int16_t(slots);
-            a.n_terms[ns] = uint8_t(cnt);
-            a.seg_update[ns] = updates(c) ? 1 : 0;
-            for (int32_t q = 0; q < cnt; ++q) {
-                const int32_t src = order ? order[size_t(c) * P + q] : q;
-                a.x[slots + q] = static_cast<const float*>(contrib[src]);
-            }
+            a.seg_info[ns] = uint32_t(slots) | (uint32_t(cnt) << 16) | (updates(c) ? (1u << 24) : 0u);
+            pointer_list(c, slots);
             slots += cnt;
             blocks += nblk;
             a.first_block[ns + 1] = int32_t(blocks);
@@ -410,9 +294,7 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
         for (int i = slots; i < kPtrSlots; ++i) a.x[i] = nullptr;
         for (int i = ns; i < kMaxSegs; ++i) {
             a.lo[i] = a.hi[i] = 0;
-            a.x_begin[i] = 0;
-            a.n_terms[i] = 0;
-            a.seg_update[i] = 0;
+            a.seg_info[i] = 0;
             a.first_block[i + 1] = a.first_block[ns];
         }
         a.n_segs = ns;
@@ -455,6 +337,47 @@ mc::UpdatePlan immediate(float lr, float mu, float wd) {
 }  // namespace
 
 namespace mc {
+
+int check_order(const mc_layout* L, int32_t P, const int32_t* order) {
+    if (!L || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if (order) {
+        for (int32_t c = 0; c < L->k; ++c) {
+            uint64_t seen = 0;
+            for (int32_t q = 0; q < P; ++q) {
+                const int32_t o = order[size_t(c) * P + q];
+                if (o < 0 || o >= P || (seen >> o) & 1) return MC_ERR_INVALID_ARG;
+                seen |= uint64_t(1) << o;
+            }
+        }
+    }
+    return MC_OK;
+}
+
+int check_flat_buffers(const mc_layout* L, const void* const* contrib, int32_t P, const void* grad_out,
+                       const void* weights, const void* momentum, bool needs_state, bool needs_g) {
+    if (!L || !contrib || P < 1 || P > MC_MAX_P) return MC_ERR_INVALID_ARG;
+    if (needs_state && (!weights || !momentum)) return MC_ERR_INVALID_ARG;
+    if (needs_g && !grad_out) return MC_ERR_INVALID_ARG;
+    for (int32_t p = 0; p < P; ++p)
+        if (!contrib[p]) return MC_ERR_INVALID_ARG;
+    const void* written[3];
+    int nw = 0;
+    if (weights) written[nw++] = weights;
+    if (momentum) written[nw++] = momentum;
+    if (grad_out) written[nw++] = grad_out;
+    for (int32_t p = 0; p < P; ++p)
+        if (!aligned(contrib[p], 16)) return MC_ERR_ALIGN;
+    for (int i = 0; i < nw; ++i)
+        if (!aligned(written[i], 16)) return MC_ERR_ALIGN;
+    const uint64_t bytes = uint64_t(L->N) * 4;
+    for (int i = 0; i < nw; ++i) {
+        for (int j = i + 1; j < nw; ++j)
+            if (overlaps(written[i], bytes, written[j], bytes)) return MC_ERR_OVERLAP;
+        for (int32_t p = 0; p < P; ++p)
+            if (overlaps(written[i], bytes, contrib[p], bytes)) return MC_ERR_OVERLAP;
+    }
+    return MC_OK;
+}
 
 int update_plan(const mc_update_spec* spec, UpdatePlan* out) {
     if (!spec || (spec->nesterov != 0 && spec->nesterov != 1)) return MC_ERR_INVALID_ARG;

@@ -24,6 +24,9 @@ ERR_LIMIT = -6
 MAX_P = 32
 NOALLOC_MAX_TENSORS = 256
 NOALLOC_MAX_ELEMS = 1 << 28
+PACKETS_MAX_COLOURS = 32
+PACKETS_MAX_BLOCKS = 4096
+PACKETS_STATUS_WORDS = 2
 COLOUR_ALIGN_ELEMS = 256
 OPT_RU_SHAPE = 1
 OPT_STATE_POLICY = 2
@@ -33,6 +36,7 @@ OPT_ALTERNATE_SWEEP = 5
 OPT_XCD_RUN = 6
 OPT_XCD_RUN_PACK = 7
 OPT_XCD_RUN_UNPACK = 8
+OPT_DIRECT_TILES = 9
 STATE_DEFAULT, STATE_RESIDENT, STATE_STREAMING = 0, 1, 2
 SWEEP_AUTO, SWEEP_FORWARD, SWEEP_BACKWARD = 0, 1, 2
 ROLE_LEAF, ROLE_INNER, ROLE_ROOT = 0, 1, 2
@@ -76,6 +80,11 @@ SIGNATURES = {
                                            ctypes.c_int64, ctypes.c_int64, _vp]),
     "mc_fused_step_ex": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _i32p,
                                         ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp, _vp, _vp]),
+    "mc_packets_reset": (ctypes.c_int, [_vp, ctypes.c_int32, _vp, ctypes.c_int32, _vp]),
+    "mc_packet_signal": (ctypes.c_int, [_vp, ctypes.c_int32, ctypes.c_uint32, _vp]),
+    "mc_reduce_update_packets": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp, _vp,
+                                                _vp, ctypes.c_int32, _vp, ctypes.c_uint32, ctypes.c_uint32,
+                                                _vp, ctypes.c_int32, _vp]),
     "mc_hyper_write": (ctypes.c_int, [_vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, _vp]),
     "mc_lr_schedule": (ctypes.c_int, [ctypes.c_float, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                       ctypes.c_float, ctypes.c_float, ctypes.POINTER(ctypes.c_float)]),
@@ -425,6 +434,28 @@ def fused_step_ex(layout: Layout, contrib_sets, order, grad_out_ptr, weights: "T
                                 momentum.handle if momentum is not None else None,
                                 ctypes.byref(spec) if spec is not None else None, stream or None),
            "mc_fused_step_ex")
+
+
+def packets_reset(ready_ptr: Optional[int], n_packets: int, progress_ptr: Optional[int], n_blocks: int,
+                  stream: int = 0) -> None:
+    _check(lib.mc_packets_reset(ready_ptr, n_packets, progress_ptr, n_blocks, stream or None), "mc_packets_reset")
+
+
+def packet_signal(ready_ptr: Optional[int], packet: int, value: int, stream: int = 0) -> None:
+    _check(lib.mc_packet_signal(ready_ptr, packet, value, stream or None), "mc_packet_signal")
+
+
+def reduce_update_packets(layout: Layout, contrib_ptrs, order, grad_out_ptr, weights_ptr, momentum_ptr,
+                          spec: UpdateSpec, packets_ptr: Optional[int], n_packets: int, ready_ptr: Optional[int],
+                          ready_value: int, spin_limit: int, progress_ptr: Optional[int], n_blocks: int,
+                          stream: int = 0) -> None:
+    P = _count(contrib_ptrs)
+    _o, optr = _order_ptr(order, layout.k, P)
+    _check(lib.mc_reduce_update_packets(layout.handle, _ptr_table(contrib_ptrs), P, optr, grad_out_ptr,
+                                        weights_ptr, momentum_ptr,
+                                        ctypes.byref(spec) if spec is not None else None,
+                                        packets_ptr, n_packets, ready_ptr, ready_value, spin_limit,
+                                        progress_ptr, n_blocks, stream or None), "mc_reduce_update_packets")
 
 
 def hyper_write(hyper_dev_ptr: Optional[int], lr: float, mu: float, wd: float, stream: int = 0) -> None:

@@ -160,6 +160,8 @@ def test_pack_rejects_before_launch():
         assert _code(fn, [B + 2, None, B + (1 << 20)], flat) == mc.ERR_ALIGN
         assert _code(fn, [flat + 400, None, B], flat) == mc.ERR_OVERLAP
         assert _code(fn, [B, None, flat - 8], flat) == mc.ERR_OVERLAP
+    # two destination tensors of an unpack that overlap each other (fine as sources of a pack)
+    assert _code(lambda t, f: mc.unpack(L, f, t), [B, None, B + 3996], flat) == mc.ERR_OVERLAP
     assert mc.lib.mc_pack(None, None, None, None) == mc.ERR_INVALID_ARG
     assert mc.lib.mc_unpack(None, None, None, None) == mc.ERR_INVALID_ARG
     assert mc.lib.mc_layout_prepare(None) == mc.ERR_INVALID_ARG

@@ -31,6 +31,21 @@ def test_full_size_step(name, order_kind):
     torch.cuda.empty_cache()
 
 
+def test_full_size_odd_layout_staged():
+    """ResNet-50 with every tensor one element longer through mc_pack x P, mc_reduce_update and
+    mc_unpack: every flat offset after the first tensor is misaligned against the 16-byte aligned
+    tensors, so pack and unpack run their 32-bit path on the tensor side at full size."""
+    base = wl.workload("resnet50")
+    sizes = [s + 1 for s in base.sizes]
+    print(f"full size staged, odd layout N={sum(sizes)}", flush=True)
+    st = gh.Step(sizes, base.k)
+    xs = [wl.contribution_tensors(sizes, p) for p in range(base.P)]
+    gpu, ref = st.run(xs, wl.weight_tensors(sizes), wl.zero_tensors(sizes), base.lr, base.mu, base.wd,
+                      order=wl.rotation_order(base.k, base.P))
+    st.check(gpu, ref, base.lr, base.mu, base.wd, "staged odd layout")
+    torch.cuda.empty_cache()
+
+
 def test_googlenet_hundred_steps_carry_state():
     cfg = wl.workload("googlenet")
     L = mc.Layout(cfg.sizes, cfg.k)

@@ -211,7 +211,8 @@ def test_googlenet_fused_steps_carry_state():
     g = gh.dev_empty(N)
     wr = oracle.pack(O, wl.weight_tensors(cfg.sizes))
     vr = np.zeros(N, np.float32)
-    steps = 20
+    steps = cfg.steps            # the configuration's 100 back-to-back steps
+    assert steps == 100
     for step in range(steps):
         host = [wl.contribution_tensors(cfg.sizes, p, step=step) for p in range(cfg.P)]
         dev = [gh.place_tensors(h)[0] for h in host]
@@ -221,7 +222,7 @@ def test_googlenet_fused_steps_carry_state():
         for st in sets:
             st.destroy()
         gr = oracle.reduce_update(O, [oracle.pack(O, ts) for ts in host], wr, vr, cfg.lr, cfg.mu, cfg.wd, order=order)
-        if step + 1 in (1, 2, 10, steps):
+        if step + 1 in (1, 2, 50, 100):
             print(f"googlenet fused step {step + 1}", flush=True)
             gh.assert_bits(g.cpu().numpy(), gr, f"g after step {step + 1}")
             for a, b in zip(w_layers, oracle.unpack(O, wr)):

@@ -69,3 +69,64 @@ def test_staged_step_in_a_graph():
                     t.copy_(torch.from_numpy(a))
         xs = [oracle.pack(O, h) for h in host_x]
         torch.cuda.synchronize()
+
+
+def test_captured_pair_of_sweep_directions():
+    """A graph replays the kernel arguments it captured, the walking direction among them.  A
+    caller whose state exceeds the memory-side cache captures the fused step twice, once per
+    explicit direction (mc_update_spec.sweep), and alternates the two graphs; every replay must
+    give the oracle's bits, and the automatic direction must behave the same eagerly."""
+    sizes = [20_000_000, 12, 4100, 14_000_004]        # 34 M elements: 272 MB of weights + momentum
+    k, P = 4, 2
+    L = mc.Layout(sizes, k)
+    O = oracle.Layout(sizes, k)
+    N = L.N
+    assert 8 * N > (256 << 20)
+    L.prepare()
+    order = wl.rotation_order(k, P)
+    host_x = [wl.contribution_tensors(sizes, p) for p in range(P)]
+    host_w = wl.weight_tensors(sizes)
+    dev_x = [gh.place_tensors(h)[0] for h in host_x]
+    dev_w, _ = gh.place_tensors(host_w)
+    dev_v, _ = gh.place_tensors(wl.zero_tensors(sizes))
+    sets = mc.set_table([mc.TensorSet(L, gh.ptrs(d)) for d in dev_x])
+    wset, vset = mc.TensorSet(L, gh.ptrs(dev_w)), mc.TensorSet(L, gh.ptrs(dev_v))
+    g = gh.dev_empty(N)
+    main = torch.cuda.current_stream()
+    graphs = {}
+    for name, sweep in (("forward", mc.SWEEP_FORWARD), ("backward", mc.SWEEP_BACKWARD)):
+        spec = mc.update_spec(0.01, 0.9, 5e-4, state_policy=mc.STATE_RESIDENT, sweep=sweep)
+        cap = torch.cuda.Stream()
+        cap.wait_stream(main)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap):
+            mc.fused_step_ex(L, sets, order, g.data_ptr(), wset, vset, spec, int(torch.cuda.current_stream().cuda_stream))
+        torch.cuda.synchronize()
+        graphs[name] = graph
+    assert np.all(g.cpu().numpy().view(np.uint32) == 0xFFFFFFFF), "capture executed nothing"
+    xs = [oracle.pack(O, h) for h in host_x]
+    wr, vr = oracle.pack(O, host_w), np.zeros(N, np.float32)
+
+    def check(what):
+        gr = oracle.reduce_update(O, xs, wr, vr, 0.01, 0.9, 5e-4, order=order)
+        gh.assert_bits(g.cpu().numpy(), gr, f"g {what}")
+        for a, b in zip(dev_w, oracle.unpack(O, wr)):
+            gh.assert_bits(a.cpu().numpy(), b, f"w {what}")
+        for a, b in zip(dev_v, oracle.unpack(O, vr)):
+            gh.assert_bits(a.cpu().numpy(), b, f"v {what}")
+
+    for rep in range(4):
+        name = "forward" if rep % 2 == 0 else "backward"
+        print(f"replay {rep}: {name}", flush=True)
+        graphs[name].replay()
+        torch.cuda.synchronize()
+        check(f"replay {rep} ({name})")
+        g.view(torch.int32).fill_(-1)                 # eager work between replays
+        torch.cuda.synchronize()
+    # the automatic direction, eagerly, with resident state: two more steps from the same state
+    spec = mc.update_spec(0.01, 0.9, 5e-4, state_policy=mc.STATE_RESIDENT)
+    for rep in range(2):
+        mc.fused_step_ex(L, sets, order, g.data_ptr(), wset, vset, spec, int(main.cuda_stream))
+        torch.cuda.synchronize()
+        check(f"eager automatic direction, step {rep}")
