@@ -92,17 +92,21 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--only-headline", action="store_true",
                     help="skip the cold pass, the roles figures and the other four workloads")
-    ap.add_argument("--pipeline-packets", type=int, default=0,
-                    help="also run the packet-pipelined experiment with this many packets per colour")
+    ap.add_argument("--pipeline-packets", type=int, default=4,
+                    help="packets per colour of the packet-pipelined experiment (0 = skip)")
+    ap.add_argument("--arrival-gbps", type=float, default=50.0,
+                    help="packet pipeline: rate at which arriving contributions land, GB/s (50 = four 100 Gb/s adapters)")
     ap.add_argument("--roles-nodes", type=int, default=8,
                     help="time one rank's role-dependent step in a tree Allreduce over this many nodes (0 = skip)")
     ap.add_argument("--shape", type=int, default=0,
                     help="workgroup shape of the update kernels (0 = the library picks)")
     ap.add_argument("--state-policy", type=int, default=0, choices=[0, 1, 2],
-                    help="what the default state policy means (0 = by size, 1 resident, 2 streaming)")
+                    help="what the default state policy means (0 = the library's default, 1 resident, 2 streaming)")
     ap.add_argument("--state-store-sc1", type=int, default=-1, choices=[-1, 0, 1])
     ap.add_argument("--alternate-sweep", type=int, default=-1, choices=[-1, 0, 1])
     ap.add_argument("--direct-tiles", type=int, default=-1, choices=[-1, 0, 1])
+    ap.add_argument("--lds-cap-update", type=int, default=-2)
+    ap.add_argument("--lds-cap-pack", type=int, default=-2)
     ap.add_argument("--xcd-run", type=int, default=-1)
     ap.add_argument("--xcd-run-pack", type=int, default=-2)
     ap.add_argument("--xcd-run-unpack", type=int, default=-2)
@@ -299,11 +303,12 @@ def run_other_workload(H, name, order_kind, check_parity):
     state_bytes = 8 * N
     out.update({"ms_per_step": round(wall, 4), "kernel_ms": round(ev, 4), "step_bytes": bytes_,
                 "GBps": round(bytes_ / wall / 1e6, 1), "frac": round(bytes_ / ev / 1e6 / HBM_PEAK_GBPS, 4),
-                "state": ("weights + momentum (%d MB) exceed the memory-side cache: streamed" % (state_bytes >> 20))
+                "state": ("weights + momentum (%d MB) exceed the memory-side cache: kept resident as far as they "
+                          "fit, successive steps walk the payload in opposite directions" % (state_bytes >> 20))
                 if state_bytes > CACHE_BYTES else
                 ("weights + momentum (%d MB) stay cache-resident between back-to-back steps" % (state_bytes >> 20)),
                 "setup_s": round(setup_s, 1)})
-    if state_bytes <= CACHE_BYTES and name != "tiny":
+    if name != "tiny":
         cold, states, gs = cold_pass(H, I, order, K, W)
         out["cold"] = cold
         del states, gs
@@ -430,19 +435,23 @@ def roles_experiment(H, L, cfg, flats, g, w, v, n_nodes, reps):
     return out
 
 
-def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, reps):
-    """Section 4.2 pipelines the reductions packet by packet.  Here half of the P contributions
-    are resident and the other half "arrive": staging copies on a second stream stand in for
-    network buffers landing in the receive buffers.  Unpipelined: all copies, then one
-    mc_reduce_update.  Pipelined: per packet (colours interleaved, as the colours progress
-    concurrently), copy the packet of every arriving contribution, then mc_reduce_update_range
-    on it as soon as its copies are done.  On one GPU copies and sum share the same HBM, so
-    this measures latency hiding, not extra bandwidth."""
+def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, reps, arrival_gbps):
+    """Section 4.2 pipelines the reductions packet by packet: a summing rank adds a packet when it
+    arrives.  Here half of the P contributions are resident and the other half arrive: a producer
+    stream delivers them packet by packet (colours interleaved, as the colours progress concurrently)
+    into the receive buffers, paced with mc_delay to the rate of a network (`arrival_gbps` GB/s; a
+    copy inside one GPU would "arrive" faster than anything can be summed).  Three ways to consume:
+      unpipelined     wait for the last packet, then one mc_reduce_update over the whole payload;
+      event-pipelined per packet an event wait on the compute stream, then mc_reduce_update_range;
+      flag-pipelined  one resident mc_reduce_update_packets polling per-packet device flags that
+                      mc_packet_deliver raises, plus the ordered second call that finishes the rest.
+    What pipelining can win is the time from the LAST packet's arrival to the end of the step (the
+    whole sum for the unpipelined form, one packet's worth for a pipelined one): `tail_ms`."""
     torch, mc, stream = H.torch, H.mc, H.stream
     N, P, k = cfg.total, cfg.P, cfg.k
     arriving = list(range(P // 2, P))
     src = [torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3 for _ in arriving]
-    copy_stream = torch.cuda.Stream()
+    prod = torch.cuda.Stream()
     bounds = [int(b) for b in L.colour_bounds()]
     pk = []
     for c in range(k):
@@ -453,54 +462,82 @@ def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, r
         step = -(-step // 256) * 256
         pk.append([(b, min(hi, b + step)) for b in range(lo, hi, step)])
     order_of_packets = [p[j] for j in range(max(len(p) for p in pk)) for p in pk if j < len(p)]
+    n_pk = len(order_of_packets)
+    n_blocks = 1024
+    pk_dev = torch.tensor(np.array(order_of_packets, dtype=np.int64).reshape(-1), device="cuda")
+    ready = torch.zeros(n_pk, dtype=torch.int32, device="cuda")
+    progress_dev = torch.zeros(n_blocks + mc.PACKETS_STATUS_WORDS, dtype=torch.int32, device="cuda")
+    spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd)
+    mh, ph = int(stream.cuda_stream), int(prod.cuda_stream)
 
-    def pipelined(main=None):
-        main = main or stream
-        mh = int(main.cuda_stream)
-        copy_stream.wait_stream(main)
-        for (b, e) in order_of_packets:
-            with torch.cuda.stream(copy_stream):
-                for q, s_ in zip(arriving, src):
-                    mc.copy(flats[q].data_ptr() + 4 * b, s_.data_ptr() + 4 * b, 4 * (e - b), int(copy_stream.cuda_stream))
-                ev = torch.cuda.Event()
-                ev.record(copy_stream)
-            main.wait_event(ev)
+    def wire_us(b, e):
+        return max(1, int(round(len(arriving) * 4 * (e - b) / (arrival_gbps * 1e3))))
+
+    def deliver(j, b, e):
+        """One packet lands: the wire time, then the data of every arriving contribution."""
+        mc.delay(wire_us(b, e), ph)
+        for q, s_ in zip(arriving, src):
+            mc.packet_deliver(flats[q].data_ptr() + 4 * b, s_.data_ptr() + 4 * b, e - b, ready.data_ptr() + 4 * j, ph)
+
+    def unpipelined(last):
+        prod.wait_stream(stream)
+        for j, (b, e) in enumerate(order_of_packets):
+            deliver(j, b, e)
+        last.record(prod)
+        stream.wait_stream(prod)
+        mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(), cfg.lr, cfg.mu, cfg.wd, mh)
+
+    def event_pipelined(last):
+        prod.wait_stream(stream)
+        for j, (b, e) in enumerate(order_of_packets):
+            deliver(j, b, e)
+            ev = torch.cuda.Event()
+            ev.record(prod)
+            stream.wait_event(ev)
             mc.reduce_update_range(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
                                    cfg.lr, cfg.mu, cfg.wd, b, e, mh)
-        main.wait_stream(copy_stream)
+        last.record(prod)
+        stream.wait_stream(prod)
 
-    def unpipelined_own_copy(main=None):
-        main = main or stream
-        copy_stream.wait_stream(main)
-        with torch.cuda.stream(copy_stream):
-            for q, s_ in zip(arriving, src):
-                mc.copy(flats[q].data_ptr(), s_.data_ptr(), 4 * (N // 4) * 4, int(copy_stream.cuda_stream))
-        main.wait_stream(copy_stream)
-        mc.reduce_update(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
-                         cfg.lr, cfg.mu, cfg.wd, int(main.cuda_stream))
+    def flag_pipelined(last):
+        mc.packets_reset(ready.data_ptr(), n_pk, progress_dev.data_ptr(), n_blocks, mh)
+        prod.wait_stream(stream)
+
+        def reducer():
+            mc.reduce_update_packets(L, flat_table, order, g.data_ptr(), w.data_ptr(), v.data_ptr(), spec,
+                                     pk_dev.data_ptr(), n_pk, ready.data_ptr(), len(arriving), 200000,
+                                     progress_dev.data_ptr(), n_blocks, mh)
+        reducer()
+        for j, (b, e) in enumerate(order_of_packets):
+            deliver(j, b, e)
+        last.record(prod)
+        stream.wait_stream(prod)
+        reducer()
 
     def timed(fn):
-        _, ev = H.time_region(lambda i: fn(), 1, reps)
-        return ev
+        """Mean over reps of (whole step, time from the last packet's arrival to the end of the step)."""
+        tot, tail = [], []
+        for r in range(reps + 1):
+            a, last, z = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            torch.cuda.synchronize()
+            a.record(stream)
+            fn(last)
+            z.record(stream)
+            torch.cuda.synchronize()
+            if r:                                   # the first pass warms up
+                tot.append(a.elapsed_time(z))
+                tail.append(last.elapsed_time(z))
+        return round(float(np.mean(tot)), 4), round(float(np.mean(tail)), 4)
 
-    def captured(fn):
-        """The same sequence captured once into a HIP graph (kernel nodes and event edges only)
-        and replayed: removes the per-packet host cost of issuing launches and event waits."""
-        cap = torch.cuda.Stream()
-        cap.wait_stream(stream)
-        graph = torch.cuda.CUDAGraph()
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph, stream=cap):
-            fn(torch.cuda.current_stream())
-        torch.cuda.synchronize()
-        return timed(graph.replay)
-
-    out = {"packets_per_colour": packets, "n_packets": len(order_of_packets),
-           "arriving_contributions": len(arriving),
-           "unpipelined_ms": round(timed(unpipelined_own_copy), 4),
-           "pipelined_ms": round(timed(pipelined), 4)}
-    out["unpipelined_graph_ms"] = round(captured(unpipelined_own_copy), 4)
-    out["pipelined_graph_ms"] = round(captured(pipelined), 4)
+    wire_total = sum(wire_us(b, e) for b, e in order_of_packets) / 1e3
+    out = {"packets_per_colour": packets, "n_packets": n_pk, "arriving_contributions": len(arriving),
+           "arrival_GBps": arrival_gbps, "wire_ms_total": round(wire_total, 4)}
+    for name, fn in (("unpipelined", unpipelined), ("event_pipelined", event_pipelined), ("flag_pipelined", flag_pipelined)):
+        total, tail = timed(fn)
+        out[name] = {"step_ms": total, "tail_ms": tail}
+    pr = progress_dev.cpu().numpy()
+    out["flag_pipelined"]["workgroups_that_gave_up_in_last_step"] = int(pr[n_blocks])
+    out["flag_pipelined"]["complete"] = bool((pr[:n_blocks] == n_pk).all())
     return out
 
 
@@ -527,6 +564,10 @@ def main():
         mc.set_option(mc.OPT_ALTERNATE_SWEEP, args.alternate_sweep)
     if args.state_store_sc1 >= 0:
         mc.set_option(mc.OPT_STATE_STORE_SC1, args.state_store_sc1)
+    if args.lds_cap_update >= -1:
+        mc.set_option(mc.OPT_LDS_CAP_UPDATE, args.lds_cap_update)
+    if args.lds_cap_pack >= -1:
+        mc.set_option(mc.OPT_LDS_CAP_PACK, args.lds_cap_pack)
     if args.direct_tiles >= 0:
         mc.set_option(mc.OPT_DIRECT_TILES, args.direct_tiles)
     if args.xcd_run >= 0:
@@ -673,16 +714,18 @@ def main():
     I.host_sets = None
 
     pipelined = None
-    if args.pipeline_packets > 0:
+    if args.pipeline_packets > 0 and not args.only_headline and k <= mc.PACKETS_MAX_COLOURS:
+        progress(f"{cfg.name}: packet pipelines")
         pipelined = pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v,
-                                        args.pipeline_packets, reps=max(5, min(args.steps, 30)))
+                                        args.pipeline_packets, reps=max(3, min(args.steps, 10)),
+                                        arrival_gbps=args.arrival_gbps)
     roles = cold = None
     others = {}
     if not args.only_headline:
         progress(f"{cfg.name}: roles and cold-state passes")
         if args.roles_nodes > 0 and k * ((args.roles_nodes - 1 + k - 1) // k) <= args.roles_nodes:
             roles = roles_experiment(H, L, cfg, flats, g, w, v, args.roles_nodes, reps=max(5, min(args.steps, 30)))
-        if 8 * N <= CACHE_BYTES:
+        if True:
             cold, states, gs = cold_pass(H, I, order, args.steps, args.warmup)
             del states, gs
 
@@ -711,7 +754,8 @@ def main():
                    "step_bytes": step_bytes,
                    "state": "warm: steps run back to back, so weights + momentum (%d MB) %s" % (
                        (8 * N) >> 20, "stay in the 256 MB memory-side cache between steps; see roofline_cold"
-                       if 8 * N <= CACHE_BYTES else "exceed the memory-side cache and are streamed")},
+                       if 8 * N <= CACHE_BYTES else "exceed the memory-side cache; successive steps walk the payload "
+                       "in opposite directions so that the part written last is read first")},
         "pct_of_hbm_peak": round(100 * step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
         "fused_step": {"ms_per_step": round(fused_ms, 4), "kernel_ms": round(fused_k, 4),
                        "GBps": round(kernel_bytes / fused_k / 1e6, 1), "step_bytes": kernel_bytes,

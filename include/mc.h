@@ -264,10 +264,11 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
  *   one).  Any other value: MC_ERR_INVALID_ARG.
  *   state_policy and sweep change how memory is walked, never a result:
  *   state_policy (MC_STATE_*): how weights and momentum are treated in the caches.  RESIDENT keeps
- *     them cached (fastest when steps run back to back on a model whose weights + momentum fit the
- *     256 MB memory-side cache); STREAMING treats them like the contributions (fastest when they
- *     cannot be cached anyway: a forward / backward pass ran since the last step, as in Section 3,
- *     Algorithm 1, or they exceed the cache).  DEFAULT defers to MC_OPT_STATE_POLICY.
+ *     them cached: fastest when steps run back to back, most of all on a model whose weights +
+ *     momentum fit the 256 MB memory-side cache.  STREAMING treats them like the contributions:
+ *     fastest when nothing of the last step is still cached because a forward / backward pass ran in
+ *     between (Section 3, Algorithm 1: the gradients are computed, then summed, then applied).  The
+ *     library cannot see which case it is in; DEFAULT defers to MC_OPT_STATE_POLICY (resident).
  *   sweep (MC_SWEEP_*): the direction in which a whole-payload call walks the payload.  FORWARD /
  *     BACKWARD fix it (a caller that captures steps into graphs captures one of each and
  *     alternates them).  AUTO: calls with resident state larger than the memory-side cache
@@ -307,10 +308,13 @@ int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream)
  * to the caller (an event wait per packet, tens of microseconds each on this platform);
  * mc_reduce_update_packets moves it into ONE resident kernel: its workgroups walk the packets in
  * their order of arrival and, before touching packet j, poll the device-memory flag ready[j] until it
- * equals ready_value.  Whatever delivers packet j -- a copy kernel, a peer GPU, a network adapter --
- * writes the packet's data into the contribution buffers first and the flag afterwards, with release
- * semantics at device scope; mc_packet_signal is that flag write as a kernel on a stream (ordered
- * after everything queued on that stream before it).
+ * equals arrivals x (the packet's length in elements): the flag counts the elements that have landed,
+ * `arrivals` being the number of contributions that arrive per packet.  Whatever delivers a packet --
+ * a copy kernel, a peer GPU, a network adapter -- writes the data into the contribution buffer
+ * first and then raises the flag with release semantics at device scope.  Two ways are provided:
+ * mc_packet_deliver copies n_elems fp32 from src to dst (device, 16-byte aligned, not overlapping)
+ * and adds to *flag the number of elements written, workgroup by workgroup;  mc_packet_signal stores a
+ * value into ready[packet] from a kernel on `stream`, i.e. after everything queued there before it.
  *
  * Every wait is bounded: a workgroup polls at most spin_limit times in total (about a microsecond
  * apart) and then stops; no packet is ever left half-summed.  progress (device, n_blocks +
@@ -329,7 +333,7 @@ int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream)
  * packets: device, 2 * n_packets int64: begin and end of each packet in arrival order; each must be
  *   a range as mc_reduce_update_range requires and lie inside one colour; the packets of a step
  *   must be disjoint and should cover the payload.  (Device arrays cannot be validated on the host.)
- * ready: device, n_packets uint32.  n_blocks: workgroups of 256 threads, 1..MC_PACKETS_MAX_BLOCKS;
+ * ready: device, n_packets uint32.  arrivals: >= 1.  n_blocks: workgroups of 256 threads, 1..MC_PACKETS_MAX_BLOCKS;
  *   fewer leave compute units free for the producer's kernels (1024 is a good start).
  * Every colour adds all P terms and updates (order, spec, grad_out as in mc_reduce_update_ex).
  * Limits: at most MC_PACKETS_MAX_COLOURS colours and k_colours * P <= 256 (MC_ERR_LIMIT).
@@ -339,10 +343,11 @@ int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream)
 #define MC_PACKETS_STATUS_WORDS 2
 int mc_packets_reset(uint32_t* ready, int32_t n_packets, uint32_t* progress, int32_t n_blocks, void* stream);
 int mc_packet_signal(uint32_t* ready, int32_t packet, uint32_t value, void* stream);
+int mc_packet_deliver(void* dst, const void* src, int64_t n_elems, uint32_t* flag, void* stream);
 int mc_reduce_update_packets(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
                              void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
                              const int64_t* packets, int32_t n_packets, const uint32_t* ready,
-                             uint32_t ready_value, uint32_t spin_limit, uint32_t* progress, int32_t n_blocks,
+                             uint32_t arrivals, uint32_t spin_limit, uint32_t* progress, int32_t n_blocks,
                              void* stream);
 
 /* The schedule of Section 5 as a function of the position in training, in epochs (fractions
@@ -364,6 +369,10 @@ int mc_lr_schedule(float base_lr, int32_t batch_per_gpu, int32_t n_workers, floa
  * hardware counters are calibrated against.  Errors: MC_ERR_INVALID_ARG, MC_ERR_ALIGN,
  * MC_ERR_OVERLAP, MC_ERR_HIP. */
 int mc_copy(void* dst, const void* src, int64_t n_bytes, void* stream);
+/* Occupies one wavefront on `stream` for about `microseconds` (at most 100000; bounded in the kernel
+ * as well): the stand-in, in measurements, for the time a packet spends on a wire.  Not part of
+ * the method. */
+int mc_delay(uint32_t microseconds, void* stream);
 
 const char* mc_strerror(int code);     /* static string, never NULL */
 int mc_last_hip_error(void);           /* raw hipError_t of this thread's last MC_ERR_HIP */
@@ -375,9 +384,8 @@ enum {
                                       one 16-byte vector, 2 = 256 threads x two vectors; 0 (default) =
                                       chosen per launch from the size, the term count and the state
                                       policy */
-    MC_OPT_STATE_POLICY = 2,       /* what MC_STATE_DEFAULT means: MC_STATE_RESIDENT, MC_STATE_STREAMING,
-                                      or 0 (default) = resident when weights + momentum fit the 256 MB
-                                      memory-side cache, else streaming */
+    MC_OPT_STATE_POLICY = 2,       /* what MC_STATE_DEFAULT means: MC_STATE_RESIDENT (default) or
+                                      MC_STATE_STREAMING */
     MC_OPT_PACK_NONTEMPORAL = 3,   /* pack/unpack: bit 0 streaming access to the per-layer
                                       tensors, bit 1 streaming access to the flat payload
                                       (non-temporal loads, write-through stores) */
@@ -392,9 +400,14 @@ enum {
     MC_OPT_XCD_RUN_PACK = 7,       /* the same for mc_pack / mc_pack_set; -1 (default) = chosen from the
                                       payload size */
     MC_OPT_XCD_RUN_UNPACK = 8,     /* the same for mc_unpack / mc_unpack_set */
-    MC_OPT_DIRECT_TILES = 9        /* 0 / 1 (default 1): launches with 256-element tiles map a workgroup
+    MC_OPT_DIRECT_TILES = 9,       /* 0 / 1 (default 1): launches with 256-element tiles map a workgroup
                                       to its colour by dividing the tile index by the chunk length
                                       instead of searching a per-launch table */
+    MC_OPT_LDS_CAP_UPDATE = 10,    /* bytes of unused LDS reserved per workgroup of reduce_update and
+                                      fused_step (0..65536), which caps the workgroups resident per
+                                      compute unit and so the number of loads in flight; -1 (default)
+                                      = 16 wavefronts per compute unit; 0 = no cap */
+    MC_OPT_LDS_CAP_PACK = 11       /* the same for pack, unpack and mc_copy; default 0 (no cap) */
 };
 int mc_set_option(int option, int value);
 int mc_get_option(int option, int* value);

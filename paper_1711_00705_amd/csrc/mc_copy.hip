@@ -48,7 +48,7 @@ extern "C" int mc_copy(void* dst, const void* src, int64_t n_bytes, void* stream
     const int64_t per_block = int64_t(kThreads) * kVecPerThread;
     const int64_t blocks = (n_vec + per_block - 1) / per_block;
     if (blocks > 0x7fffffff) return MC_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(copy_kernel, dim3(unsigned(blocks)), dim3(kThreads), 0,
+    hipLaunchKernelGGL(copy_kernel, dim3(unsigned(blocks)), dim3(kThreads), mc::lds_reservation(MC_OPT_LDS_CAP_PACK, kThreads),
                        static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
                        static_cast<const uint4*>(src), n_vec);
     MC_HIP_TRY(hipGetLastError());

@@ -132,9 +132,11 @@ __device__ __forceinline__ void one_element(const float* const* const* xs, int n
 // element, so gp is not 16-byte aligned (g is stored word by word) and the tile has one vector
 // less (n_vec); the few elements before and after the vectors are done by the caller.
 // SS: weights and momentum are streamed instead of kept resident (see mc_update.h).
+// xp: for a compile-time term count, the P operand addresses of the tile's first vector, already
+// resolved by the caller (so that their table lookups are issued together, not one after another).
 template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS, bool SHIFTED>
-__device__ __forceinline__ void uniform_tile(const float* const* const* xs, int np, int32_t t0, int64_t rel,
-                                             float* wp, float* vp, float* gp, int n_vec,
+__device__ __forceinline__ void uniform_tile(const float* const* xp, const float* const* const* xs, int np,
+                                             int32_t t0, int64_t rel, float* wp, float* vp, float* gp, int n_vec,
                                              const mc::Hyper& hp) {
     int64_t j[U];
     bool on[U];
@@ -149,7 +151,7 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
         float4 t[P > 0 ? P : 1][U];
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            const float* xq = xs[q][t0] + rel;
+            const float* xq = xp[q];
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (on[u]) t[q][u] = load4<true>(xq + j[u]);
@@ -248,30 +250,58 @@ __device__ __forceinline__ void uniform_tile(const float* const* const* xs, int 
 // P > 0: compile-time number of terms; P == 0: run-time count np.
 // UPDATE: the SGD step follows the sum; otherwise only the sum is written to g (the colours of
 // which this rank is a leaf or inner node) and weights / momentum are never touched.
+// xb / wb / vb: for a compile-time term count, the operands' addresses of tensor t0 (element 0), looked
+// up by the caller together with the tensor's bounds; unused (null) for a run-time count.
 template <int P, int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
 __device__ __forceinline__ void fused_tile(const TileArgs a, const float* const* const* xs, int np,
                                            int64_t base, int64_t end, int32_t t0, int64_t t0_begin,
-                                           int64_t t0_end, const mc::Hyper& hp) {
+                                           int64_t t0_end, const float* const* xb, float* wb, float* vb,
+                                           const mc::Hyper& hp) {
     static_assert(HAS_G || UPDATE, "a tile must produce something");
     constexpr int kTile = THREADS * 4 * U;
     if (end - base == kTile && end <= t0_end) {
         // Whole tile inside tensor t0.  If every operand has the same offset from a 16-byte
         // boundary (all zero for a CNN payload; equal and non-zero after an odd-sized tensor,
         // because frameworks align the tensors themselves), the tile runs on 128-bit accesses.
+        // All operand addresses are looked up first, independently of one another, and compared
+        // afterwards without early exits: the lookups then travel together instead of each
+        // waiting for the previous one's verdict.
         const int64_t rel = base - t0_begin;
-        float* wp = UPDATE ? a.w[t0] + rel : nullptr;
-        float* vp = UPDATE ? a.v[t0] + rel : nullptr;
-        const int m = misalignment(xs[0][t0] + rel);
-        bool same = !UPDATE || (misalignment(wp) == m && misalignment(vp) == m);
-        for (int q = 1; q < np; ++q) same = same && misalignment(xs[q][t0] + rel) == m;
+        if (P == 0 && UPDATE) {
+            wb = a.w[t0];
+            vb = a.v[t0];
+        }
+        const float* xp[P > 0 ? P : 1];
+        if (P > 0) {
+#pragma unroll
+            for (int q = 0; q < P; ++q) xp[q] = xb[q];
+        }
+        float* wp = UPDATE ? wb + rel : nullptr;
+        float* vp = UPDATE ? vb + rel : nullptr;
+        int m;
+        bool same = true;
+        if (P > 0) {
+#pragma unroll
+            for (int q = 0; q < P; ++q) xp[q] += rel;
+            m = misalignment(xp[0]);
+#pragma unroll
+            for (int q = 1; q < P; ++q) same &= misalignment(xp[q]) == m;
+        } else {
+            xp[0] = nullptr;
+            m = misalignment(xs[0][t0] + rel);
+            for (int q = 1; q < np; ++q) same &= misalignment(xs[q][t0] + rel) == m;
+        }
+        if (UPDATE) same &= (misalignment(wp) == m) & (misalignment(vp) == m);
         if (same && m == 0) {
-            uniform_tile<P, U, THREADS, HAS_G, UPDATE, SS, false>(xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
+            uniform_tile<P, U, THREADS, HAS_G, UPDATE, SS, false>(xp, xs, np, t0, rel, wp, vp, a.g + base, kTile / 4, hp);
             return;
         }
         if (same) {
             const int head = 4 - m;               // elements up to the operands' 16-byte boundary
             const int n_vec = kTile / 4 - 1;      // whole vectors after it
-            uniform_tile<P, U, THREADS, HAS_G, UPDATE, SS, true>(xs, np, t0, rel + head, UPDATE ? wp + head : nullptr,
+#pragma unroll
+            for (int q = 0; q < (P > 0 ? P : 1); ++q) xp[q] += head;
+            uniform_tile<P, U, THREADS, HAS_G, UPDATE, SS, true>(xp, xs, np, t0, rel + head, UPDATE ? wp + head : nullptr,
                                                                  UPDATE ? vp + head : nullptr, a.g + base + head,
                                                                  n_vec, hp);
             // the `head` elements before the vectors and the `4 - head` after them
@@ -335,13 +365,24 @@ template <int U, int THREADS, bool HAS_G, bool UPDATE, bool SS>
 __device__ __forceinline__ void fused_tile_any(const TileArgs a, const float* const* const* xs, int np,
                                                int64_t base, int64_t end, int32_t t0, int64_t t0_begin,
                                                int64_t t0_end, const mc::Hyper& hp) {
-#define MC_FUSED_CASE(N) \
-    case N: fused_tile<N, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp); break
+    // per-segment launches look the operands up here, once the term count is known
+#define MC_FUSED_CASE(N)                                                                                   \
+    case N: {                                                                                              \
+        const float* xb[N];                                                                                \
+        _Pragma("unroll") for (int q = 0; q < N; ++q) xb[q] = xs[q][t0];                                   \
+        float* wb = UPDATE ? a.w[t0] : nullptr;                                                            \
+        float* vb = UPDATE ? a.v[t0] : nullptr;                                                            \
+        fused_tile<N, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, xb, wb, vb, hp); \
+        break;                                                                                             \
+    }
     switch (np) {
         MC_FUSED_CASE(2);
         MC_FUSED_CASE(4);
         MC_FUSED_CASE(8);
-        default: fused_tile<0, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, hp); break;
+        default:
+            fused_tile<0, U, THREADS, HAS_G, UPDATE, SS>(a, xs, np, base, end, t0, t0_begin, t0_end, nullptr, nullptr,
+                                                         nullptr, hp);
+            break;
     }
 #undef MC_FUSED_CASE
 }
@@ -371,11 +412,24 @@ __global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Pr
     const float* const* const* xs = a.x + (direct_uniform ? s * (P > 0 ? P : Prt) : int(a.seg_info[s] & 0xffffu));
 
     // The tensor holding the tile's first element (block-uniform).  `base` is a multiple of the
-    // lookup granularity, so the table entry is that tensor itself: no scan of off[] is needed and
-    // the loads of its bounds and of the operands' base pointers do not wait for one another.
+    // lookup granularity, so the table entry is that tensor itself: no scan of off[] is needed.
     const int32_t t0 = a.first_tensor[base / mc::kLookupElems];
-    const int64_t t0_begin = a.off[t0];
-    const int64_t t0_end = a.off[t0 + 1];
+    typedef long long ll2 __attribute__((ext_vector_type(2)));
+    ll2 t0_bounds;
+    __builtin_memcpy(&t0_bounds, a.off + t0, sizeof(t0_bounds));   // both bounds in one 16-byte load
+    const int64_t t0_begin = t0_bounds.x;
+    const int64_t t0_end = t0_bounds.y;
+    const float* xb[P > 0 ? P : 1];
+    float* wb = nullptr;
+    float* vb = nullptr;
+    if (P > 0 && MODE != kPerSegment) {
+#pragma unroll
+        for (int q = 0; q < P; ++q) xb[q] = xs[q][t0];
+        if (MODE != kSumOnly) {
+            wb = a.w[t0];
+            vb = a.v[t0];
+        }
+    }
 
     const TileArgs ta = {a.w, a.v, a.g, a.off};
     if (MODE == kPerSegment) {
@@ -392,14 +446,101 @@ __global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Pr
     } else {
         const int np = P > 0 ? P : Prt;
         fused_tile<P, U, THREADS, MODE != kUpdateOnly, MODE != kSumOnly, SS>(ta, xs, np, base, end, t0, t0_begin,
-                                                                             t0_end, hp);
+                                                                             t0_end, xb, wb, vb, hp);
+    }
+}
+
+// The common launch -- direct tile mapping, every colour adding the same compile-time number of
+// terms, one wavefront per 256-element tile -- with its lookups arranged in two batches, each issued
+// as a whole before any of it is waited for:
+//   1. what depends only on the tile index: the tile's tensor and the colour's P pointer tables;
+//   2. what depends only on that tensor: its bounds and the P + 2 operand addresses.
+// The decision which path the tile takes is ONE expression over all of them, evaluated without
+// early exits, so every lookup is needed -- and therefore issued -- before the branch.  (Every
+// dependent scalar load is a round trip of hundreds of cycles; left to source order, to early exits
+// and to the compiler's habit of deferring a load into the branch that uses it, a tile had ten of
+// them in a row in front of its first vector load: time a wavefront spends with nothing in flight.)
+template <int P, int MODE, bool SS>
+__global__ __launch_bounds__(64) void fused_direct_kernel(FusedArgs a) {
+    static_assert(P > 0 && MODE != kPerSegment, "uniform launches with a compile-time term count");
+    constexpr int kTile = MC_COLOUR_ALIGN_ELEMS;
+    constexpr bool HAS_G = MODE != kUpdateOnly, UPDATE = MODE != kSumOnly;
+    const mc::Hyper hp = mc::resolve(a.up);
+    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
+    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
+
+    // batch 1
+    const int32_t t0 = a.first_tensor[blk];                     // tile == lookup granularity
+    const int s = int(uint32_t(blk) / uint32_t(a.tiles_per_colour));
+    const float* const* const* xs = a.x + s * P;
+    const float* const* xt[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) xt[q] = xs[q];
+    __builtin_amdgcn_sched_barrier(0);
+
+    // batch 2
+    typedef long long ll2 __attribute__((ext_vector_type(2)));
+    ll2 t0_bounds;
+    __builtin_memcpy(&t0_bounds, a.off + t0, sizeof(t0_bounds));
+    const float* xb[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) xb[q] = xt[q][t0];
+    float* wb = UPDATE ? a.w[t0] : nullptr;
+    float* vb = UPDATE ? a.v[t0] : nullptr;
+    __builtin_amdgcn_sched_barrier(0);
+
+    const int64_t base = int64_t(blk) * kTile;
+    const int64_t colour_end = int64_t(s + 1) * a.tiles_per_colour * kTile;
+    const int64_t hi = colour_end < a.range_hi ? colour_end : a.range_hi;
+    const int64_t end = base + kTile < hi ? base + kTile : hi;
+    const int64_t rel = base - t0_bounds.x;
+    // whole tile inside tensor t0 and every operand 16-byte aligned there?
+    uintptr_t low_bits = 0;
+#pragma unroll
+    for (int q = 0; q < P; ++q) low_bits |= reinterpret_cast<uintptr_t>(xb[q] + rel);
+    if (UPDATE) low_bits |= reinterpret_cast<uintptr_t>(wb + rel) | reinterpret_cast<uintptr_t>(vb + rel);
+    const bool fast = (end - base == kTile) & (end <= t0_bounds.y) & ((low_bits & 15) == 0);
+    if (fast) {
+        const float* xp[P];
+#pragma unroll
+        for (int q = 0; q < P; ++q) xp[q] = xb[q] + rel;
+        uniform_tile<P, 1, 64, HAS_G, UPDATE, SS, false>(xp, xs, P, t0, rel, UPDATE ? wb + rel : nullptr,
+                                                          UPDATE ? vb + rel : nullptr, a.g + base, kTile / 4, hp);
+        return;
+    }
+    const TileArgs ta = {a.w, a.v, a.g, a.off};
+    fused_tile<P, 1, 64, HAS_G, UPDATE, SS>(ta, xs, P, base, end, t0, t0_bounds.x, t0_bounds.y, xb, wb, vb, hp);
+}
+
+template <int P>
+void launch_direct_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
+    const dim3 grid(blocks), block(64);
+#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_direct_kernel<P, MODE, SS>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a)
+    switch (mode) {
+        case kSumOnly: MC_FUSED_LAUNCH(kSumOnly, false); break;
+        case kUpdateAndG: if (ss) MC_FUSED_LAUNCH(kUpdateAndG, true); else MC_FUSED_LAUNCH(kUpdateAndG, false); break;
+        default: if (ss) MC_FUSED_LAUNCH(kUpdateOnly, true); else MC_FUSED_LAUNCH(kUpdateOnly, false); break;
+    }
+#undef MC_FUSED_LAUNCH
+}
+
+void launch_direct(int P, int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
+    switch (P) {
+        case 1: launch_direct_mode<1>(mode, ss, blocks, s, a); break;
+        case 2: launch_direct_mode<2>(mode, ss, blocks, s, a); break;
+        case 3: launch_direct_mode<3>(mode, ss, blocks, s, a); break;
+        case 4: launch_direct_mode<4>(mode, ss, blocks, s, a); break;
+        case 5: launch_direct_mode<5>(mode, ss, blocks, s, a); break;
+        case 6: launch_direct_mode<6>(mode, ss, blocks, s, a); break;
+        case 7: launch_direct_mode<7>(mode, ss, blocks, s, a); break;
+        default: launch_direct_mode<8>(mode, ss, blocks, s, a); break;
     }
 }
 
 template <int P, int U, int T>
 void launch_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
     const dim3 grid(blocks), block(T);
-#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_step_kernel<P, U, T, MODE, SS>), grid, block, 0, s, a, Prt)
+#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_step_kernel<P, U, T, MODE, SS>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, T), s, a, Prt)
     switch (mode) {
         case kSumOnly: MC_FUSED_LAUNCH(kSumOnly, false); break;   // state is not touched: one policy
         case kUpdateAndG: if (ss) MC_FUSED_LAUNCH(kUpdateAndG, true); else MC_FUSED_LAUNCH(kUpdateAndG, false); break;
@@ -435,9 +576,9 @@ void launch(int P, mc::Shape shape, int mode, bool ss, unsigned blocks, hipStrea
 void launch_per_segment(bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
     const dim3 grid(blocks), block(64);
     if (ss)
-        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, true>), grid, block, 0, s, a, 0);
+        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, true>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
     else
-        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, false>), grid, block, 0, s, a, 0);
+        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, false>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
 }
 
 // Do two sorted lists of [begin, end) spans intersect anywhere?
@@ -620,8 +761,10 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     // the 256-element runs of the payload and a tile's colour is its index divided by the chunk
     // length.  Needs every colour's pointer list in the one launch.
     const int64_t tiles_total = (L->N + tile - 1) / tile;
-    const int slots_needed = (uniform && !any_skipped) ? L->k * terms(first_active) : total_terms;
-    if (tile == MC_COLOUR_ALIGN_ELEMS && L->k <= kMaxSegs && slots_needed <= kPtrSlots &&
+    // (A call whose colours agree but for some it skips keeps the table, which simply leaves the
+    // skipped colours out and still runs the compile-time body.)
+    const int slots_needed = uniform ? L->k * terms(first_active) : total_terms;
+    if (tile == MC_COLOUR_ALIGN_ELEMS && !(uniform && any_skipped) && L->k <= kMaxSegs && slots_needed <= kPtrSlots &&
         tiles_total < 0x7fffffff && mc::option(MC_OPT_DIRECT_TILES) != 0) {
         a.tiles_per_colour = int32_t(L->chunk / tile);
         a.n_segs = L->k;
@@ -632,7 +775,7 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             a.first_block[i] = 0;
         }
         a.first_block[kMaxSegs] = 0;
-        const bool per_segment = !uniform || any_skipped;
+        const bool per_segment = !uniform;
         int slots = 0;
         for (int32_t c = 0; c < L->k; ++c) {
             if (!per_segment) {
@@ -647,7 +790,10 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             launch_per_segment(ss, unsigned(tiles_total), s, a);
         } else {
             const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
-            launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);
+            if (terms(first_active) <= 8)
+                launch_direct(terms(first_active), mode, ss, unsigned(tiles_total), s, a);
+            else
+                launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);
         }
         MC_HIP_TRY(hipGetLastError());
         return MC_OK;

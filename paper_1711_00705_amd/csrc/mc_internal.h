@@ -92,9 +92,29 @@ struct Shape {
 // are within 1 % of it.  So it is the default for every launch; MC_OPT_RU_SHAPE = 2 forces 256 x 2.
 Shape shape_for(int64_t elems, int n_terms, bool stream_state);
 
+// Bytes of (unused) dynamic LDS to reserve per workgroup, which caps how many workgroups a compute
+// unit holds at once.  These kernels need no LDS; the reservation is a throttle.  With every wave
+// slot filled (32 per compute unit) a streaming kernel keeps about 50 MB of loads in flight across
+// the chip, spread over a 5-6 MB window of each of its streams, far more than the 12-16 MB that
+// cover HBM's latency -- and the wider the window, the fewer requests find their DRAM row still open.
+// A bare loop with this access mix (64-thread workgroups, one 16-byte vector per thread and stream)
+// is fastest at 8 wavefronts per compute unit: +3-5 % on a cold ResNet-50-sized step, +6-7 % at
+// VGG-16 size, +2-3 % warm.  The real kernels have scalar table lookups in front of each tile's
+// loads and need more wavefronts to hide them: measured on the fused step, 16 per compute unit
+// (10 KB per 64-thread workgroup) against no cap: cold ResNet-50 76.1 -> 77.4 % of peak, VGG-16
+// 75.1 -> 77.4 %, warm ResNet-50 and the eight-contribution step unchanged, GoogLeNet -0.7 point;
+// 12 KB gains two more points at VGG-16 size but loses four on the warm step; 8 per compute unit
+// loses everywhere except VGG-16.  The automatic setting is therefore 16 per compute unit.
+// `which`: MC_OPT_LDS_CAP_UPDATE or MC_OPT_LDS_CAP_PACK (copy-shaped kernels only lose with a cap:
+// default none); `threads` per workgroup of the launch.
+unsigned lds_reservation(int which, int threads);
+
 // Cache treatment of weights and momentum for a call on layout L: `policy` is the caller's
-// MC_STATE_* value (MC_STATE_DEFAULT defers to MC_OPT_STATE_POLICY, whose automatic setting goes
-// by whether weights + momentum fit the 256 MB memory-side cache).
+// MC_STATE_* value (MC_STATE_DEFAULT defers to MC_OPT_STATE_POLICY).  The library cannot know
+// whether anything ran between two steps, so the default is the policy that suits steps run back to
+// back (resident: +15 % on the ResNet-50-sized step, and with alternating sweeps still +3 % on the
+// VGG-16-sized one whose state is four times the cache); a caller whose steps are separated by a
+// forward / backward pass asks for streaming (+6 % when the state is cold).
 bool stream_state(const mc_layout* L, int policy);
 
 // Should this whole-payload update call walk the payload backwards?  `sweep` is the caller's

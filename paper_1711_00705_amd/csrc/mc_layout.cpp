@@ -10,7 +10,7 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 std::atomic<int> g_ru_shape{0};
-std::atomic<int> g_state_policy{0};
+std::atomic<int> g_state_policy{MC_STATE_RESIDENT};
 std::atomic<int> g_pack_nontemporal{3};
 std::atomic<int> g_state_store_sc1{1};
 std::atomic<int> g_alternate_sweep{1};
@@ -18,6 +18,8 @@ std::atomic<int> g_xcd_run{0};
 std::atomic<int> g_xcd_run_pack{-1};
 std::atomic<int> g_xcd_run_unpack{0};
 std::atomic<int> g_direct_tiles{1};
+std::atomic<int> g_lds_cap_update{-1};
+std::atomic<int> g_lds_cap_pack{0};
 
 // Capacity of the memory-side cache that sits between the L2s and HBM.
 constexpr int64_t kMemorySideCacheBytes = int64_t(256) << 20;
@@ -41,11 +43,17 @@ Shape shape_for(int64_t elems, int n_terms, bool stream_state) {
     return Shape{64, 1};
 }
 
+unsigned lds_reservation(int which, int threads) {
+    int v = (which == MC_OPT_LDS_CAP_PACK ? g_lds_cap_pack : g_lds_cap_update).load(std::memory_order_relaxed);
+    // automatic: 16 wavefronts per compute unit (10 KB of the 160 KB per wavefront of the workgroup)
+    if (v < 0) v = 10240 * (threads / 64);
+    return unsigned(v);
+}
+
 bool stream_state(const mc_layout* L, int policy) {
+    (void)L;
     if (policy == MC_STATE_DEFAULT) policy = g_state_policy.load(std::memory_order_relaxed);
-    if (policy == MC_STATE_RESIDENT) return false;
-    if (policy == MC_STATE_STREAMING) return true;
-    return L->N * 8 > kMemorySideCacheBytes;   // weights + momentum: 8 bytes per element
+    return policy == MC_STATE_STREAMING;
 }
 
 bool sweep_reversed(const mc_layout* L, int sweep, bool stream_state) {
@@ -69,6 +77,8 @@ int option(int which) {
         case MC_OPT_XCD_RUN_PACK: return g_xcd_run_pack.load(std::memory_order_relaxed);
         case MC_OPT_XCD_RUN_UNPACK: return g_xcd_run_unpack.load(std::memory_order_relaxed);
         case MC_OPT_DIRECT_TILES: return g_direct_tiles.load(std::memory_order_relaxed);
+        case MC_OPT_LDS_CAP_UPDATE: return g_lds_cap_update.load(std::memory_order_relaxed);
+        case MC_OPT_LDS_CAP_PACK: return g_lds_cap_pack.load(std::memory_order_relaxed);
         default: return kNoSuchOption;
     }
 }
@@ -174,7 +184,7 @@ int mc_set_option(int option, int value) {
             g_ru_shape.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_STATE_POLICY:
-            if (value != 0 && value != MC_STATE_RESIDENT && value != MC_STATE_STREAMING) return MC_ERR_INVALID_ARG;
+            if (value != MC_STATE_RESIDENT && value != MC_STATE_STREAMING) return MC_ERR_INVALID_ARG;
             g_state_policy.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_PACK_NONTEMPORAL:
@@ -200,6 +210,14 @@ int mc_set_option(int option, int value) {
         case MC_OPT_XCD_RUN_UNPACK:
             if (value < -1 || value > 64) return MC_ERR_INVALID_ARG;
             g_xcd_run_unpack.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_LDS_CAP_UPDATE:
+            if (value < -1 || value > 65536) return MC_ERR_INVALID_ARG;
+            g_lds_cap_update.store(value, std::memory_order_relaxed);
+            return MC_OK;
+        case MC_OPT_LDS_CAP_PACK:
+            if (value < -1 || value > 65536) return MC_ERR_INVALID_ARG;
+            g_lds_cap_pack.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_DIRECT_TILES:
             if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;

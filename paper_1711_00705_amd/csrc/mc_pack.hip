@@ -177,13 +177,14 @@ int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch&
     // and unpack, which often re-reads what an update has just written, loses with it.
     int xcd_run = mc::option(UNPACK ? MC_OPT_XCD_RUN_UNPACK : MC_OPT_XCD_RUN_PACK);
     if (xcd_run < 0) xcd_run = (!UNPACK && vec == 1) ? 16 : 0;
+    const unsigned lds = mc::lds_reservation(MC_OPT_LDS_CAP_PACK, kThreads);
 #define MC_GS_LAUNCH(NT_T, NT_F)                                                                       \
     do {                                                                                               \
         if (vec == 2)                                                                                  \
-            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, 0, s, batch, \
+            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, lds, s, batch, \
                                table, dt->off, dt->tile_first, f, t0, t1, tile0, xcd_run);             \
         else                                                                                           \
-            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, 0, s, batch, \
+            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, lds, s, batch, \
                                table, dt->off, dt->tile_first, f, t0, t1, tile0, xcd_run);             \
     } while (0)
     switch (nt & 3) {

@@ -36,7 +36,7 @@ struct PkArgs {
     int32_t n_colours;
     int32_t np;
     int32_t n_packets;
-    uint32_t ready_value;
+    uint32_t arrivals;
     uint32_t spin_limit;
     int64_t N;
     const int64_t* packets;               // device: begin, end of each packet, in arrival order
@@ -58,11 +58,22 @@ __global__ __launch_bounds__(kThreads) void packet_reducer_kernel(PkArgs a) {
     uint32_t j = a.progress[blockIdx.x];          // where an earlier launch of this step stopped
     bool gave_up = false;
     for (; j < uint32_t(a.n_packets); ++j) {
+        // Packet j has landed when its flag equals arrivals x its length in elements: every delivery
+        // adds the number of elements it wrote (mc_packet_deliver), or the producer writes the final
+        // value at once (mc_packet_signal).  A malformed descriptor is not waited for.
+        const int64_t lo = a.packets[2 * int64_t(j)];
+        const int64_t hi = a.packets[2 * int64_t(j) + 1];
+        const bool well_formed = lo >= 0 && lo < hi && hi <= a.N && lo % MC_COLOUR_ALIGN_ELEMS == 0;
         if (threadIdx.x == 0) {
             int ok = 0;
+            const uint32_t want = a.arrivals * uint32_t(hi - lo);
             for (;;) {
+                if (!well_formed) {
+                    ok = 1;
+                    break;
+                }
                 const uint32_t f = __hip_atomic_load(a.ready + j, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                if (f == a.ready_value) {
+                if (f == want) {
                     ok = 1;
                     break;
                 }
@@ -82,10 +93,8 @@ __global__ __launch_bounds__(kThreads) void packet_reducer_kernel(PkArgs a) {
         // The flag was read by one thread; every wave makes the packet's data visible to itself.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 
-        const int64_t lo = a.packets[2 * int64_t(j)];
-        const int64_t hi = a.packets[2 * int64_t(j) + 1];
         int c = -1;
-        if (lo >= 0 && lo < hi && hi <= a.N && lo % MC_COLOUR_ALIGN_ELEMS == 0) {
+        if (well_formed) {
             for (int i = 0; i < a.n_colours; ++i)
                 if (a.bounds[i] <= lo && hi <= a.bounds[i + 1]) c = i;
         }
@@ -114,6 +123,34 @@ __global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t value) {
 __global__ void signal_kernel(uint32_t* flag, uint32_t value) {
     if (threadIdx.x == 0 && blockIdx.x == 0)
         __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Copies n elements and then adds, per workgroup, the number of elements that workgroup wrote to
+// *flag (release at device scope: the data is visible before the count).
+__global__ __launch_bounds__(kThreads) void deliver_kernel(float* dst, const float* src, int64_t n, uint32_t* flag) {
+    const int64_t base = int64_t(blockIdx.x) * kTile;
+    const int64_t i = base + int64_t(threadIdx.x) * 4;
+    if (i + 4 <= n) {
+        *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(src + i);
+    } else {
+        for (int64_t e = i; e < n; ++e) dst[e] = src[e];
+    }
+    __syncthreads();                               // every store of the workgroup is issued
+    if (threadIdx.x == 0) {
+        const int64_t mine = (n - base < kTile) ? n - base : kTile;
+        __hip_atomic_fetch_add(flag, uint32_t(mine), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Occupies one wavefront for about `us` microseconds (bounded by the caller): stands in for the time a
+// packet spends on a wire.
+__global__ void delay_kernel(uint32_t us) {
+    const uint64_t t0 = wall_clock64();            // 100 MHz
+    const uint64_t ticks = uint64_t(us) * 100;
+    for (uint32_t i = 0; i < us * 4 + 16; ++i) {   // bounded whatever the clock does
+        if (wall_clock64() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(16);
+    }
 }
 
 template <int P>
@@ -158,16 +195,37 @@ int mc_packet_signal(uint32_t* ready, int32_t packet, uint32_t value, void* stre
     return MC_OK;
 }
 
+int mc_packet_deliver(void* dst, const void* src, int64_t n_elems, uint32_t* flag, void* stream) {
+    if (n_elems < 0) return MC_ERR_INVALID_ARG;
+    if (n_elems == 0) return MC_OK;
+    if (!dst || !src || !flag) return MC_ERR_INVALID_ARG;
+    if (!mc::aligned(dst, 16) || !mc::aligned(src, 16) || !mc::aligned(flag, 4)) return MC_ERR_ALIGN;
+    if (mc::overlaps(dst, uint64_t(n_elems) * 4, src, uint64_t(n_elems) * 4)) return MC_ERR_OVERLAP;
+    const int64_t blocks = (n_elems + kTile - 1) / kTile;
+    if (blocks > 0x7fffffff || n_elems > 0xffffffffll) return MC_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(deliver_kernel, dim3(unsigned(blocks)), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<float*>(dst), static_cast<const float*>(src), n_elems, flag);
+    MC_HIP_TRY(hipGetLastError());
+    return MC_OK;
+}
+
+int mc_delay(uint32_t microseconds, void* stream) {
+    if (microseconds > 100000) return MC_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), microseconds);
+    MC_HIP_TRY(hipGetLastError());
+    return MC_OK;
+}
+
 int mc_reduce_update_packets(const mc_layout* L, const void* const* contrib, int32_t P, const int32_t* order,
                              void* grad_out, void* weights, void* momentum, const mc_update_spec* spec,
                              const int64_t* packets, int32_t n_packets, const uint32_t* ready,
-                             uint32_t ready_value, uint32_t spin_limit, uint32_t* progress, int32_t n_blocks,
+                             uint32_t arrivals, uint32_t spin_limit, uint32_t* progress, int32_t n_blocks,
                              void* stream) {
     if (!L) return MC_ERR_INVALID_ARG;
     mc::UpdatePlan plan;
     int rc = mc::update_plan(spec, &plan);
     if (rc != MC_OK) return rc;
-    if (n_packets < 0 || n_blocks < 1 || n_blocks > MC_PACKETS_MAX_BLOCKS) return MC_ERR_INVALID_ARG;
+    if (n_packets < 0 || n_blocks < 1 || n_blocks > MC_PACKETS_MAX_BLOCKS || arrivals < 1) return MC_ERR_INVALID_ARG;
     if (L->k > kMaxColours || int64_t(L->k) * P > kPtrSlots) return MC_ERR_LIMIT;
     if (plan.up.hyper && !mc::aligned(plan.up.hyper, 4)) return MC_ERR_ALIGN;
     rc = mc::check_order(L, P, order);
@@ -188,7 +246,7 @@ int mc_reduce_update_packets(const mc_layout* L, const void* const* contrib, int
     a.n_colours = L->k;
     a.np = P;
     a.n_packets = n_packets;
-    a.ready_value = ready_value;
+    a.arrivals = arrivals;
     a.spin_limit = spin_limit;
     a.N = L->N;
     a.packets = packets;

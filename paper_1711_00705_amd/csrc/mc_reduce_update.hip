@@ -120,7 +120,7 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
 template <int P, int U, int T>
 void launch_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
     const dim3 grid(blocks), block(T);
-#define MC_RU_LAUNCH(MODE, SS) hipLaunchKernelGGL((reduce_update_kernel<P, U, T, MODE, SS>), grid, block, 0, s, a, Prt)
+#define MC_RU_LAUNCH(MODE, SS) hipLaunchKernelGGL((reduce_update_kernel<P, U, T, MODE, SS>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, T), s, a, Prt)
     switch (mode) {
         case kSumOnly: MC_RU_LAUNCH(kSumOnly, false); break;   // state is not touched: one policy
         case kUpdateAndG: if (ss) MC_RU_LAUNCH(kUpdateAndG, true); else MC_RU_LAUNCH(kUpdateAndG, false); break;
@@ -156,9 +156,9 @@ void launch(int P, mc::Shape shape, int mode, bool ss, unsigned blocks, hipStrea
 void launch_per_segment(bool ss, unsigned blocks, hipStream_t s, const RuArgs& a) {
     const dim3 grid(blocks), block(64);
     if (ss)
-        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, true>), grid, block, 0, s, a, 0);
+        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, true>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
     else
-        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, false>), grid, block, 0, s, a, 0);
+        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, false>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
 }
 
 // Shared by every entry point.  n_terms / do_update are null for the uniform call (every
@@ -230,8 +230,10 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     // the 256-element runs of [r_lo, r_hi) and a tile's colour is its index divided by the chunk
     // length.  Needs every colour's pointer list in the one launch.
     const int64_t tiles_total = (r_hi - r_lo + tile - 1) / tile;
-    const int slots_needed = (uniform && !any_skipped) ? L->k * terms(first_active) : total_terms;
-    if (tile == MC_COLOUR_ALIGN_ELEMS && L->k <= kMaxSegs && slots_needed <= kPtrSlots &&
+    // (A call whose colours agree but for some it skips keeps the table, which simply leaves the
+    // skipped colours out and still runs the compile-time body.)
+    const int slots_needed = uniform ? L->k * terms(first_active) : total_terms;
+    if (tile == MC_COLOUR_ALIGN_ELEMS && !(uniform && any_skipped) && L->k <= kMaxSegs && slots_needed <= kPtrSlots &&
         tiles_total <= 0x7fffffff && L->N / tile < 0x7fffffff && mc::option(MC_OPT_DIRECT_TILES) != 0) {
         a.tiles_per_colour = int32_t(L->chunk / tile);
         a.first_tile = uint32_t(r_lo / tile);
@@ -243,7 +245,7 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
             a.first_block[i] = 0;
         }
         a.first_block[kMaxSegs] = 0;
-        const bool per_segment = !uniform || any_skipped;
+        const bool per_segment = !uniform;
         int slots = 0;
         for (int32_t c = 0; c < L->k; ++c) {
             if (!per_segment) {

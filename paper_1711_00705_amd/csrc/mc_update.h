@@ -40,16 +40,21 @@ struct Hyper {
     bool state_store_sc1;
 };
 
+// The immediate values sit in the kernel's argument block and arrive through scalar loads.  The
+// device triple is read through a volatile pointer on purpose: with two plain loads the compiler
+// turns "argument block or device memory" into ONE vector load through a selected address, and that
+// load -- issued by every wavefront, from an argument block that may live in host memory -- is then
+// in front of every tile even when no device triple is in use.
 __device__ __forceinline__ Hyper resolve(const UpdateParams& p) {
     Hyper h;
+    h.lr = p.lr;
+    h.mu = p.mu;
+    h.wd = p.wd;
     if (p.hyper) {
-        h.lr = p.hyper[0];
-        h.mu = p.hyper[1];
-        h.wd = p.hyper[2];
-    } else {
-        h.lr = p.lr;
-        h.mu = p.mu;
-        h.wd = p.wd;
+        const volatile float* dev = p.hyper;
+        h.lr = dev[0];
+        h.mu = dev[1];
+        h.wd = dev[2];
     }
     h.nesterov = p.nesterov != 0;
     h.state_store_sc1 = p.state_store_sc1 != 0;

@@ -37,6 +37,8 @@ OPT_XCD_RUN = 6
 OPT_XCD_RUN_PACK = 7
 OPT_XCD_RUN_UNPACK = 8
 OPT_DIRECT_TILES = 9
+OPT_LDS_CAP_UPDATE = 10
+OPT_LDS_CAP_PACK = 11
 STATE_DEFAULT, STATE_RESIDENT, STATE_STREAMING = 0, 1, 2
 SWEEP_AUTO, SWEEP_FORWARD, SWEEP_BACKWARD = 0, 1, 2
 ROLE_LEAF, ROLE_INNER, ROLE_ROOT = 0, 1, 2
@@ -82,6 +84,8 @@ SIGNATURES = {
                                         ctypes.POINTER(ctypes.c_uint8), _vp, _vp, _vp, _vp, _vp]),
     "mc_packets_reset": (ctypes.c_int, [_vp, ctypes.c_int32, _vp, ctypes.c_int32, _vp]),
     "mc_packet_signal": (ctypes.c_int, [_vp, ctypes.c_int32, ctypes.c_uint32, _vp]),
+    "mc_packet_deliver": (ctypes.c_int, [_vp, _vp, ctypes.c_int64, _vp, _vp]),
+    "mc_delay": (ctypes.c_int, [ctypes.c_uint32, _vp]),
     "mc_reduce_update_packets": (ctypes.c_int, [_vp, _vpp, ctypes.c_int32, _i32p, _vp, _vp, _vp, _vp,
                                                 _vp, ctypes.c_int32, _vp, ctypes.c_uint32, ctypes.c_uint32,
                                                 _vp, ctypes.c_int32, _vp]),
@@ -445,16 +449,25 @@ def packet_signal(ready_ptr: Optional[int], packet: int, value: int, stream: int
     _check(lib.mc_packet_signal(ready_ptr, packet, value, stream or None), "mc_packet_signal")
 
 
+def packet_deliver(dst_ptr: Optional[int], src_ptr: Optional[int], n_elems: int, flag_ptr: Optional[int],
+                   stream: int = 0) -> None:
+    _check(lib.mc_packet_deliver(dst_ptr, src_ptr, n_elems, flag_ptr, stream or None), "mc_packet_deliver")
+
+
+def delay(microseconds: int, stream: int = 0) -> None:
+    _check(lib.mc_delay(microseconds, stream or None), "mc_delay")
+
+
 def reduce_update_packets(layout: Layout, contrib_ptrs, order, grad_out_ptr, weights_ptr, momentum_ptr,
                           spec: UpdateSpec, packets_ptr: Optional[int], n_packets: int, ready_ptr: Optional[int],
-                          ready_value: int, spin_limit: int, progress_ptr: Optional[int], n_blocks: int,
+                          arrivals: int, spin_limit: int, progress_ptr: Optional[int], n_blocks: int,
                           stream: int = 0) -> None:
     P = _count(contrib_ptrs)
     _o, optr = _order_ptr(order, layout.k, P)
     _check(lib.mc_reduce_update_packets(layout.handle, _ptr_table(contrib_ptrs), P, optr, grad_out_ptr,
                                         weights_ptr, momentum_ptr,
                                         ctypes.byref(spec) if spec is not None else None,
-                                        packets_ptr, n_packets, ready_ptr, ready_value, spin_limit,
+                                        packets_ptr, n_packets, ready_ptr, arrivals, spin_limit,
                                         progress_ptr, n_blocks, stream or None), "mc_reduce_update_packets")
 
 

@@ -178,13 +178,16 @@ def test_empty_payload_is_a_no_op():
 def test_options():
     assert mc.get_option(mc.OPT_RU_SHAPE) in (0, 1, 2)
     for opt, good, bad in ((mc.OPT_RU_SHAPE, (0, 1, 2), (-1, 3, 4)),
-                           (mc.OPT_STATE_POLICY, (0, 1, 2), (-1, 3)),
+                           (mc.OPT_STATE_POLICY, (1, 2), (-1, 0, 3)),
                            (mc.OPT_PACK_NONTEMPORAL, (0, 1, 2, 3), (-1, 4)),
                            (mc.OPT_STATE_STORE_SC1, (0, 1), (-1, 2)),
                            (mc.OPT_ALTERNATE_SWEEP, (0, 1), (-1, 2)),
                            (mc.OPT_XCD_RUN, (0, 1, 8, 64), (-1, 65)),
                            (mc.OPT_XCD_RUN_PACK, (-1, 0, 16, 64), (-2, 65)),
-                           (mc.OPT_XCD_RUN_UNPACK, (-1, 0, 16, 64), (-2, 65))):
+                           (mc.OPT_XCD_RUN_UNPACK, (-1, 0, 16, 64), (-2, 65)),
+                           (mc.OPT_DIRECT_TILES, (0, 1), (-1, 2)),
+                           (mc.OPT_LDS_CAP_UPDATE, (-1, 0, 20480, 65536), (-2, 65537)),
+                           (mc.OPT_LDS_CAP_PACK, (-1, 0, 20480, 65536), (-2, 65537))):
         keep = mc.get_option(opt)
         for g in good:
             mc.set_option(opt, g)

@@ -62,10 +62,15 @@ class Case:
         self.v = gh.to_dev(self.v_host)
         self.g = gh.dev_empty(self.L.N)
 
-    def reduce(self, x_dev, spin_limit, stream):
+    def reduce(self, x_dev, spin_limit, stream, arrivals=1):
         mc.reduce_update_packets(self.L, [x.data_ptr() for x in x_dev], self.order, self.g.data_ptr(),
                                  self.w.data_ptr(), self.v.data_ptr(), self.spec, self.pk_dev.data_ptr(), self.n,
-                                 self.ready.data_ptr(), 1, spin_limit, self.progress.data_ptr(), N_BLOCKS, stream)
+                                 self.ready.data_ptr(), arrivals, spin_limit, self.progress.data_ptr(), N_BLOCKS, stream)
+
+    def signal(self, j, stream, arrivals=1):
+        """The flag of packet j counts the elements that have landed: set it to its final value."""
+        b, e = self.pk[j]
+        mc.packet_signal(self.ready.data_ptr(), j, arrivals * (e - b), stream)
 
     def check_complete(self, what):
         pr = self.progress.cpu().numpy()
@@ -84,7 +89,7 @@ def test_all_flags_already_set():
     print(f"packets: {c.n} packets, all flags set beforehand", flush=True)
     mc.packets_reset(c.ready.data_ptr(), c.n, c.progress.data_ptr(), N_BLOCKS, s)
     for j in range(c.n):
-        mc.packet_signal(c.ready.data_ptr(), j, 1, s)
+        c.signal(j, s)
     c.reduce(x_dev, 1000, s)
     torch.cuda.synchronize()
     assert c.progress.cpu().numpy()[N_BLOCKS] == 0, "no workgroup should have had to give up"
@@ -107,7 +112,7 @@ def test_flags_that_never_come_then_resume():
     # half of the packets arrive: a second call gets exactly that far
     half = c.n // 2
     for j in range(half):
-        mc.packet_signal(c.ready.data_ptr(), j, 1, s)
+        c.signal(j, s)
     c.reduce(x_dev, 5, s)
     torch.cuda.synchronize()
     pr = c.progress.cpu().numpy()
@@ -120,7 +125,7 @@ def test_flags_that_never_come_then_resume():
     gh.assert_bits(w_now[~done], c.w_host[~done], "packets that did not arrive are untouched")
     # the rest arrives
     for j in range(half, c.n):
-        mc.packet_signal(c.ready.data_ptr(), j, 1, s)
+        c.signal(j, s)
     c.reduce(x_dev, 5, s)
     torch.cuda.synchronize()
     c.check_complete("resumed after giving up twice")
@@ -138,20 +143,15 @@ def test_producer_on_a_second_stream():
     print(f"packets: {c.n} packets delivered by copies on a second stream", flush=True)
     mc.packets_reset(c.ready.data_ptr(), c.n, c.progress.data_ptr(), N_BLOCKS, s)
     prod.wait_stream(main)
-    c.reduce(x_dev, 20000, s)                      # about 20 ms of patience in total per workgroup
+    c.reduce(x_dev, 20000, s, arrivals=len(arriving))     # about 20 ms of patience in total per workgroup
     for j, (b, e) in enumerate(c.pk):
-        n_bytes = (e - b) * 4
-        whole = n_bytes // 16 * 16
-        for p in arriving:
-            mc.copy(x_dev[p].data_ptr() + 4 * b, src[p].data_ptr() + 4 * b, whole, ps)
-            if whole != n_bytes:                   # the payload's ragged end: a torch copy of the last words
-                with torch.cuda.stream(prod):
-                    x_dev[p][b + whole // 4:e].copy_(src[p][b + whole // 4:e])
-        mc.packet_signal(c.ready.data_ptr(), j, 1, ps)
+        for p in arriving:                          # each delivery adds the elements it wrote to the packet's flag
+            mc.packet_deliver(x_dev[p].data_ptr() + 4 * b, src[p].data_ptr() + 4 * b, e - b,
+                              c.ready.data_ptr() + 4 * j, ps)
     done = torch.cuda.Event()
     done.record(prod)
     main.wait_event(done)
-    c.reduce(x_dev, 20000, s)                      # finishes whatever the first launch gave up on
+    c.reduce(x_dev, 20000, s, arrivals=len(arriving))     # finishes whatever the first launch gave up on
     torch.cuda.synchronize()
     print(f"workgroups that gave up in the first launch: {int(c.progress.cpu().numpy()[N_BLOCKS])} of {N_BLOCKS}", flush=True)
     c.check_complete("producer on a second stream")
@@ -162,7 +162,7 @@ def test_rejects_before_launch():
     c.fresh_state()
     x = [gh.to_dev(xh) for xh in c.x_host]
     ptrs = [t.data_ptr() for t in x]
-    args = dict(packets_ptr=c.pk_dev.data_ptr(), n_packets=c.n, ready_ptr=c.ready.data_ptr(), ready_value=1,
+    args = dict(packets_ptr=c.pk_dev.data_ptr(), n_packets=c.n, ready_ptr=c.ready.data_ptr(), arrivals=1,
                 spin_limit=1, progress_ptr=c.progress.data_ptr())
 
     def code(**kw):
@@ -174,6 +174,7 @@ def test_rejects_before_launch():
             return e.code
         return mc.OK
     assert code(n_blocks=0) == mc.ERR_INVALID_ARG
+    assert code(arrivals=0) == mc.ERR_INVALID_ARG
     assert code(n_blocks=mc.PACKETS_MAX_BLOCKS + 1) == mc.ERR_INVALID_ARG
     assert code(packets_ptr=None) == mc.ERR_INVALID_ARG
     assert code(ready_ptr=None) == mc.ERR_INVALID_ARG
@@ -183,3 +184,18 @@ def test_rejects_before_launch():
         mc.reduce_update_packets(big, ptrs, None, None, c.w.data_ptr(), c.v.data_ptr(), c.spec, n_blocks=8, **args)
     assert e.value.code == mc.ERR_LIMIT
     torch.cuda.synchronize()
+
+
+def test_deliver_counts_elements_and_delay_returns():
+    n = 5 * 1024 + 3                               # ragged: the last workgroup copies 3 words one by one
+    src = gh.to_dev(np.arange(n, dtype=np.float32))
+    dst = gh.dev_empty(n + 8)
+    flag = torch.zeros(2, dtype=torch.int32, device="cuda")
+    s = gh.stream_handle()
+    mc.delay(200, s)
+    mc.packet_deliver(dst.data_ptr(), src.data_ptr(), n, flag.data_ptr() + 4, s)
+    torch.cuda.synchronize()
+    assert flag.cpu().tolist() == [0, n]
+    out = dst.cpu().numpy()
+    gh.assert_bits(out[:n], np.arange(n, dtype=np.float32), "delivered words")
+    assert np.all(out[n:].view(np.uint32) == 0xFFFFFFFF), "wrote past the packet"

@@ -16,7 +16,7 @@ import gpu_harness as gh  # noqa: E402
 
 N_CASES = int(os.environ.get("MC_RANDOM_CASES", "24"))
 OPTS = (mc.OPT_RU_SHAPE, mc.OPT_STATE_POLICY, mc.OPT_PACK_NONTEMPORAL, mc.OPT_STATE_STORE_SC1, mc.OPT_XCD_RUN,
-        mc.OPT_XCD_RUN_PACK, mc.OPT_XCD_RUN_UNPACK)
+        mc.OPT_XCD_RUN_PACK, mc.OPT_XCD_RUN_UNPACK, mc.OPT_DIRECT_TILES, mc.OPT_LDS_CAP_UPDATE, mc.OPT_LDS_CAP_PACK)
 
 
 @pytest.fixture(autouse=True)
@@ -45,11 +45,14 @@ def _case(seed):
     P = int(rng.choice([1, 2, 3, 4, 5, 8, 11, 32]))
     order = [None, wl.rotation_order(k, P), wl.random_order(k, P, seed=seed)][int(rng.integers(0, 3))]
     misalign = [None, [0], [int(x) for x in rng.integers(0, 4, size=5)]][int(rng.integers(0, 3))]
-    opts = {mc.OPT_RU_SHAPE: int(rng.choice([0, 1, 2])), mc.OPT_STATE_POLICY: int(rng.integers(0, 3)),
+    opts = {mc.OPT_RU_SHAPE: int(rng.choice([0, 1, 2])), mc.OPT_STATE_POLICY: int(rng.integers(1, 3)),
             mc.OPT_PACK_NONTEMPORAL: int(rng.integers(0, 4)), mc.OPT_STATE_STORE_SC1: int(rng.integers(0, 2))}
     opts[mc.OPT_XCD_RUN] = int(rng.choice([0, 0, 2, 3, 8, 64]))
     opts[mc.OPT_XCD_RUN_PACK] = int(rng.choice([-1, 0, 2, 16, 64]))
     opts[mc.OPT_XCD_RUN_UNPACK] = int(rng.choice([-1, 0, 3, 16]))
+    opts[mc.OPT_DIRECT_TILES] = int(rng.integers(0, 2))
+    opts[mc.OPT_LDS_CAP_UPDATE] = int(rng.choice([-1, 0, 4096, 40960]))
+    opts[mc.OPT_LDS_CAP_PACK] = int(rng.choice([-1, 0, 8192]))
     hyper = [float(x) for x in (rng.choice([0.1, 0.01, 0.5]), rng.choice([0.9, 0.0, 0.5]), rng.choice([1e-4, 0.0, 5e-4]))]
     return sizes, k, P, order, misalign, opts, hyper, rng
 
