@@ -94,6 +94,8 @@ def parse():
                     help="skip the cold pass, the roles figures and the other four workloads")
     ap.add_argument("--pipeline-packets", type=int, default=4,
                     help="packets per colour of the packet-pipelined experiment (0 = skip)")
+    ap.add_argument("--packet-blocks", type=int, default=256,
+                    help="packet pipeline: workgroups of the resident reducer")
     ap.add_argument("--arrival-gbps", type=float, default=50.0,
                     help="packet pipeline: rate at which arriving contributions land, GB/s (50 = four 100 Gb/s adapters)")
     ap.add_argument("--roles-nodes", type=int, default=8,
@@ -435,7 +437,7 @@ def roles_experiment(H, L, cfg, flats, g, w, v, n_nodes, reps):
     return out
 
 
-def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, reps, arrival_gbps):
+def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, reps, arrival_gbps, blocks=256):
     """Section 4.2 pipelines the reductions packet by packet: a summing rank adds a packet when it
     arrives.  Here half of the P contributions are resident and the other half arrive: a producer
     stream delivers them packet by packet (colours interleaved, as the colours progress concurrently)
@@ -463,7 +465,7 @@ def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, r
         pk.append([(b, min(hi, b + step)) for b in range(lo, hi, step)])
     order_of_packets = [p[j] for j in range(max(len(p) for p in pk)) for p in pk if j < len(p)]
     n_pk = len(order_of_packets)
-    n_blocks = 1024
+    n_blocks = blocks
     pk_dev = torch.tensor(np.array(order_of_packets, dtype=np.int64).reshape(-1), device="cuda")
     ready = torch.zeros(n_pk, dtype=torch.int32, device="cuda")
     progress_dev = torch.zeros(n_blocks + mc.PACKETS_STATUS_WORDS, dtype=torch.int32, device="cuda")
@@ -531,7 +533,7 @@ def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, r
 
     wire_total = sum(wire_us(b, e) for b, e in order_of_packets) / 1e3
     out = {"packets_per_colour": packets, "n_packets": n_pk, "arriving_contributions": len(arriving),
-           "arrival_GBps": arrival_gbps, "wire_ms_total": round(wire_total, 4)}
+           "reducer_workgroups": n_blocks, "arrival_GBps": arrival_gbps, "wire_ms_total": round(wire_total, 4)}
     for name, fn in (("unpipelined", unpipelined), ("event_pipelined", event_pipelined), ("flag_pipelined", flag_pipelined)):
         total, tail = timed(fn)
         out[name] = {"step_ms": total, "tail_ms": tail}
@@ -718,7 +720,7 @@ def main():
         progress(f"{cfg.name}: packet pipelines")
         pipelined = pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v,
                                         args.pipeline_packets, reps=max(3, min(args.steps, 10)),
-                                        arrival_gbps=args.arrival_gbps)
+                                        arrival_gbps=args.arrival_gbps, blocks=args.packet_blocks)
     roles = cold = None
     others = {}
     if not args.only_headline:

@@ -316,9 +316,9 @@ int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream)
  * and adds to *flag the number of elements written, workgroup by workgroup;  mc_packet_signal stores a
  * value into ready[packet] from a kernel on `stream`, i.e. after everything queued there before it.
  *
- * Every wait is bounded: a workgroup polls at most spin_limit times in total (about a microsecond
- * apart) and then stops; no packet is ever left half-summed.  progress (device, n_blocks +
- * MC_PACKETS_STATUS_WORDS uint32) records per workgroup how many packets it has completed; a later
+ * Every wait is bounded: a workgroup polls at most spin_limit times in total (half a microsecond to
+ * four microseconds apart, backing off while it waits) and then stops; no packet is ever left
+ * half-summed.  progress (device, n_blocks + MC_PACKETS_STATUS_WORDS uint32) records per workgroup how many packets it has completed; a later
  * call with the same packets, flags, progress and n_blocks resumes every workgroup from its own
  * count.  The protocol of one step:
  *   mc_packets_reset(ready, n_packets, progress, n_blocks, stream)         -- zero both
@@ -333,8 +333,10 @@ int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream)
  * packets: device, 2 * n_packets int64: begin and end of each packet in arrival order; each must be
  *   a range as mc_reduce_update_range requires and lie inside one colour; the packets of a step
  *   must be disjoint and should cover the payload.  (Device arrays cannot be validated on the host.)
- * ready: device, n_packets uint32.  arrivals: >= 1.  n_blocks: workgroups of 256 threads, 1..MC_PACKETS_MAX_BLOCKS;
- *   fewer leave compute units free for the producer's kernels (1024 is a good start).
+ * ready: device, n_packets uint32.  arrivals: >= 1.  n_blocks: workgroups of 256 threads, at least 1
+ *   and at most twice the device's compute units (MC_ERR_LIMIT beyond: all workgroups have to be
+ *   resident together and still leave wave slots to the kernels that deliver packets, or each side
+ *   waits for the other until the poll budget ends).  One per compute unit is a good choice.
  * Every colour adds all P terms and updates (order, spec, grad_out as in mc_reduce_update_ex).
  * Limits: at most MC_PACKETS_MAX_COLOURS colours and k_colours * P <= 256 (MC_ERR_LIMIT).
  * Errors otherwise as mc_reduce_update_ex. */

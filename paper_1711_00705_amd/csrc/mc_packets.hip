@@ -66,20 +66,29 @@ __global__ __launch_bounds__(kThreads) void packet_reducer_kernel(PkArgs a) {
         const bool well_formed = lo >= 0 && lo < hi && hi <= a.N && lo % MC_COLOUR_ALIGN_ELEMS == 0;
         if (threadIdx.x == 0) {
             int ok = 0;
+            int nap = 0;
             const uint32_t want = a.arrivals * uint32_t(hi - lo);
             for (;;) {
                 if (!well_formed) {
                     ok = 1;
                     break;
                 }
-                const uint32_t f = __hip_atomic_load(a.ready + j, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                // relaxed on purpose: an acquire here would invalidate the caches on every poll of
+                // every workgroup; the one acquire that matters follows once the flag has been seen
+                const uint32_t f = __hip_atomic_load(a.ready + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (f == want) {
                     ok = 1;
                     break;
                 }
                 if (polls_left == 0) break;
                 --polls_left;
-                __builtin_amdgcn_s_sleep(32);     // about a microsecond
+                // back off: a packet that is about to land is seen within a microsecond, a long wait
+                // costs the memory system one request per workgroup every four microseconds
+                if (nap == 0) __builtin_amdgcn_s_sleep(16);
+                else if (nap == 1) __builtin_amdgcn_s_sleep(32);
+                else if (nap == 2) __builtin_amdgcn_s_sleep(64);
+                else __builtin_amdgcn_s_sleep(127);
+                if (nap < 3) ++nap;
             }
             go = ok;
         }
@@ -90,7 +99,8 @@ __global__ __launch_bounds__(kThreads) void packet_reducer_kernel(PkArgs a) {
             gave_up = true;
             break;
         }
-        // The flag was read by one thread; every wave makes the packet's data visible to itself.
+        // The flag was read (relaxed) by one thread; every wave now acquires at device scope, which
+        // makes the packet's data, written before the flag was raised, visible to its loads.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 
         int c = -1;
@@ -235,6 +245,13 @@ int mc_reduce_update_packets(const mc_layout* L, const void* const* contrib, int
     if (n_packets == 0) return MC_OK;
     if (!packets || !ready || !progress) return MC_ERR_INVALID_ARG;
     if (!mc::aligned(packets, 8) || !mc::aligned(ready, 4) || !mc::aligned(progress, 4)) return MC_ERR_ALIGN;
+    // Every workgroup must be resident at once AND leave wave slots to whatever delivers the packets:
+    // a grid that fills the device would wait for a producer that cannot start, until the poll budget
+    // ends.  Two workgroups (8 of 32 wave slots) per compute unit is the most that is accepted.
+    int dev = 0, cus = 0;
+    MC_HIP_TRY(hipGetDevice(&dev));
+    MC_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_blocks > 2 * cus) return MC_ERR_LIMIT;
 
     PkArgs a;
     for (int32_t c = 0; c < L->k; ++c)

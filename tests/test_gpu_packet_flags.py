@@ -179,6 +179,11 @@ def test_rejects_before_launch():
     assert code(packets_ptr=None) == mc.ERR_INVALID_ARG
     assert code(ready_ptr=None) == mc.ERR_INVALID_ARG
     assert code(progress_ptr=None) == mc.ERR_INVALID_ARG
+    # a grid that could not be resident beside the producer's kernels is refused, not left to time out
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    room = torch.zeros(2 * cus + 1 + mc.PACKETS_STATUS_WORDS, dtype=torch.int32, device="cuda")
+    assert code(n_blocks=2 * cus, progress_ptr=room.data_ptr()) == mc.OK
+    assert code(n_blocks=2 * cus + 1, progress_ptr=room.data_ptr()) == mc.ERR_LIMIT
     big = mc.Layout([1000] * 40, 40)
     with pytest.raises(mc.McError) as e:
         mc.reduce_update_packets(big, ptrs, None, None, c.w.data_ptr(), c.v.data_ptr(), c.spec, n_blocks=8, **args)
