@@ -136,7 +136,7 @@ int mc_pack_noalloc(const mc_layout* L, const void* const* tensors, void* flat, 
  *     w[i] = w[i] - lr * v[i]                      (uses the NEW v)
  *     grad_out[i] = g                              (if grad_out != NULL)
  *
- * every operation rounded once to fp32.  The paper gives no update formula ("perform SGD");
+ * every operation rounded once to fp32.  The paper gives no update formula (only that SGD is performed);
  * this is heavy-ball momentum with L2 decay folded into the gradient, dampening 0.
  *
  * contrib:  host array of P device pointers, each N fp32 flat, 16-byte aligned.  By
@@ -408,7 +408,9 @@ enum {
     MC_OPT_LDS_CAP_UPDATE = 10,    /* bytes of unused LDS reserved per workgroup of reduce_update and
                                       fused_step (0..65536), which caps the workgroups resident per
                                       compute unit and so the number of loads in flight; -1 (default)
-                                      = 16 wavefronts per compute unit; 0 = no cap */
+                                      = by the call: 16 wavefronts per compute unit when weights and
+                                      momentum are expected in the memory-side cache, 12 when they
+                                      are streamed, 8 when they exceed the cache; 0 = no cap */
     MC_OPT_LDS_CAP_PACK = 11       /* the same for pack, unpack and mc_copy; default 0 (no cap) */
 };
 int mc_set_option(int option, int value);

@@ -16,6 +16,8 @@ HIPCC_FLAGS = (
     "-ffp-contract=off",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # leading scalar kernel arguments arrive in registers at wavefront start instead of through loads
+    "-mllvm", "-amdgpu-kernarg-preload-count=14",
     "-Wall", "-Wno-unused-command-line-argument",
 )
 

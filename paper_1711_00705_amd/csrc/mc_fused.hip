@@ -53,6 +53,8 @@ struct FusedArgs {
     const int64_t* off;                 // n+1 flat offsets
     const int32_t* first_tensor;        // lookup: first tensor per kLookupElems flat elements
     mc::UpdateParams up;
+    uint32_t lds_per_wave;              // host only: dynamic LDS reserved by a launch of 64-thread workgroups
+    uint32_t lds_per_4waves;            //            ... of 256-thread workgroups (an occupancy cap, nothing is stored there)
 };
 
 typedef float native_f4 __attribute__((ext_vector_type(4)));
@@ -461,37 +463,45 @@ __global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Pr
 // and to the compiler's habit of deferring a load into the branch that uses it, a tile had ten of
 // them in a row in front of its first vector load: time a wavefront spends with nothing in flight.)
 template <int P, int MODE, bool SS>
-__global__ __launch_bounds__(64) void fused_direct_kernel(FusedArgs a) {
+__global__ __launch_bounds__(64) void fused_direct_kernel(const int32_t* __restrict__ first_tensor,
+                                                          const int64_t* __restrict__ off, float* const* w,
+                                                          float* const* v, float* g, int32_t tiles_per_colour,
+                                                          int32_t flip, int64_t range_hi, FusedArgs a) {
+    // The eight scalars in front of the argument block are what a tile needs before its first
+    // lookup; as leading arguments they are delivered in registers when the wavefront starts
+    // (kernel-argument preload), so no load stands between the launch and batch 1.
+    // flip: index of the last tile when the launch walks backwards, -1 otherwise.
     static_assert(P > 0 && MODE != kPerSegment, "uniform launches with a compile-time term count");
     constexpr int kTile = MC_COLOUR_ALIGN_ELEMS;
     constexpr bool HAS_G = MODE != kUpdateOnly, UPDATE = MODE != kSumOnly;
-    const mc::Hyper hp = mc::resolve(a.up);
-    const int tile = mc::xcd_tile(int(blockIdx.x), int(gridDim.x), a.xcd_run);
-    const int blk = a.reverse ? int(gridDim.x) - 1 - tile : tile;
+    const int blk = flip >= 0 ? flip - int(blockIdx.x) : int(blockIdx.x);
 
-    // batch 1
-    const int32_t t0 = a.first_tensor[blk];                     // tile == lookup granularity
-    const int s = int(uint32_t(blk) / uint32_t(a.tiles_per_colour));
+    // batch 1 (the argument-block fetches first: nothing here may wait for the table lookup)
+    const int s = int(uint32_t(blk) / uint32_t(tiles_per_colour));
     const float* const* const* xs = a.x + s * P;
     const float* const* xt[P];
 #pragma unroll
     for (int q = 0; q < P; ++q) xt[q] = xs[q];
+    const mc::UpdateParams up = a.up;
+    __builtin_amdgcn_sched_barrier(0);
+    const int32_t t0 = first_tensor[blk];                       // tile == lookup granularity
     __builtin_amdgcn_sched_barrier(0);
 
     // batch 2
     typedef long long ll2 __attribute__((ext_vector_type(2)));
     ll2 t0_bounds;
-    __builtin_memcpy(&t0_bounds, a.off + t0, sizeof(t0_bounds));
+    __builtin_memcpy(&t0_bounds, off + t0, sizeof(t0_bounds));
     const float* xb[P];
 #pragma unroll
     for (int q = 0; q < P; ++q) xb[q] = xt[q][t0];
-    float* wb = UPDATE ? a.w[t0] : nullptr;
-    float* vb = UPDATE ? a.v[t0] : nullptr;
+    float* wb = UPDATE ? w[t0] : nullptr;
+    float* vb = UPDATE ? v[t0] : nullptr;
     __builtin_amdgcn_sched_barrier(0);
+    const mc::Hyper hp = mc::resolve(up);
 
     const int64_t base = int64_t(blk) * kTile;
-    const int64_t colour_end = int64_t(s + 1) * a.tiles_per_colour * kTile;
-    const int64_t hi = colour_end < a.range_hi ? colour_end : a.range_hi;
+    const int64_t colour_end = int64_t(s + 1) * tiles_per_colour * kTile;
+    const int64_t hi = colour_end < range_hi ? colour_end : range_hi;
     const int64_t end = base + kTile < hi ? base + kTile : hi;
     const int64_t rel = base - t0_bounds.x;
     // whole tile inside tensor t0 and every operand 16-byte aligned there?
@@ -505,17 +515,20 @@ __global__ __launch_bounds__(64) void fused_direct_kernel(FusedArgs a) {
 #pragma unroll
         for (int q = 0; q < P; ++q) xp[q] = xb[q] + rel;
         uniform_tile<P, 1, 64, HAS_G, UPDATE, SS, false>(xp, xs, P, t0, rel, UPDATE ? wb + rel : nullptr,
-                                                          UPDATE ? vb + rel : nullptr, a.g + base, kTile / 4, hp);
+                                                          UPDATE ? vb + rel : nullptr, g + base, kTile / 4, hp);
         return;
     }
-    const TileArgs ta = {a.w, a.v, a.g, a.off};
+    const TileArgs ta = {w, v, g, off};
     fused_tile<P, 1, 64, HAS_G, UPDATE, SS>(ta, xs, P, base, end, t0, t0_bounds.x, t0_bounds.y, xb, wb, vb, hp);
 }
 
 template <int P>
 void launch_direct_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
     const dim3 grid(blocks), block(64);
-#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_direct_kernel<P, MODE, SS>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a)
+    const int32_t flip = a.reverse ? int32_t(blocks) - 1 : -1;
+#define MC_FUSED_LAUNCH(MODE, SS)                                                                                       \
+    hipLaunchKernelGGL((fused_direct_kernel<P, MODE, SS>), grid, block, a.lds_per_wave, s, \
+                       a.first_tensor, a.off, a.w, a.v, a.g, a.tiles_per_colour, flip, a.range_hi, a)
     switch (mode) {
         case kSumOnly: MC_FUSED_LAUNCH(kSumOnly, false); break;
         case kUpdateAndG: if (ss) MC_FUSED_LAUNCH(kUpdateAndG, true); else MC_FUSED_LAUNCH(kUpdateAndG, false); break;
@@ -540,7 +553,7 @@ void launch_direct(int P, int mode, bool ss, unsigned blocks, hipStream_t s, con
 template <int P, int U, int T>
 void launch_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a, int Prt) {
     const dim3 grid(blocks), block(T);
-#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_step_kernel<P, U, T, MODE, SS>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, T), s, a, Prt)
+#define MC_FUSED_LAUNCH(MODE, SS) hipLaunchKernelGGL((fused_step_kernel<P, U, T, MODE, SS>), grid, block, (T == 64 ? a.lds_per_wave : a.lds_per_4waves), s, a, Prt)
     switch (mode) {
         case kSumOnly: MC_FUSED_LAUNCH(kSumOnly, false); break;   // state is not touched: one policy
         case kUpdateAndG: if (ss) MC_FUSED_LAUNCH(kUpdateAndG, true); else MC_FUSED_LAUNCH(kUpdateAndG, false); break;
@@ -576,9 +589,9 @@ void launch(int P, mc::Shape shape, int mode, bool ss, unsigned blocks, hipStrea
 void launch_per_segment(bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
     const dim3 grid(blocks), block(64);
     if (ss)
-        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, true>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
+        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, true>), grid, block, a.lds_per_wave, s, a, 0);
     else
-        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, false>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
+        hipLaunchKernelGGL((fused_step_kernel<0, 1, 64, kPerSegment, false>), grid, block, a.lds_per_wave, s, a, 0);
 }
 
 // Do two sorted lists of [begin, end) spans intersect anywhere?
@@ -743,6 +756,8 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     // Only the plain whole-payload step alternates by itself: role calls come several to a step.
     a.reverse = mc::sweep_reversed(L, (n_terms && plan.sweep == MC_SWEEP_AUTO) ? MC_SWEEP_FORWARD : plan.sweep, ss) ? 1 : 0;
     a.xcd_run = mc::option(MC_OPT_XCD_RUN);
+    a.lds_per_wave = mc::update_lds_reservation(L, 64, ss);
+    a.lds_per_4waves = mc::update_lds_reservation(L, 256, ss);
     a.w = weights ? reinterpret_cast<float* const*>(weights->d_ptrs) : nullptr;
     a.v = momentum ? reinterpret_cast<float* const*>(momentum->d_ptrs) : nullptr;
     a.g = static_cast<float*>(grad_out);
@@ -790,7 +805,7 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             launch_per_segment(ss, unsigned(tiles_total), s, a);
         } else {
             const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
-            if (terms(first_active) <= 8)
+            if (terms(first_active) <= 8 && a.xcd_run < 2)   // (a run of tiles per die is the general kernel's)
                 launch_direct(terms(first_active), mode, ss, unsigned(tiles_total), s, a);
             else
                 launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);

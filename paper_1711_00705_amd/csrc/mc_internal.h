@@ -99,15 +99,19 @@ Shape shape_for(int64_t elems, int n_terms, bool stream_state);
 // cover HBM's latency -- and the wider the window, the fewer requests find their DRAM row still open.
 // A bare loop with this access mix (64-thread workgroups, one 16-byte vector per thread and stream)
 // is fastest at 8 wavefronts per compute unit: +3-5 % on a cold ResNet-50-sized step, +6-7 % at
-// VGG-16 size, +2-3 % warm.  The real kernels have scalar table lookups in front of each tile's
-// loads and need more wavefronts to hide them: measured on the fused step, 16 per compute unit
-// (10 KB per 64-thread workgroup) against no cap: cold ResNet-50 76.1 -> 77.4 % of peak, VGG-16
-// 75.1 -> 77.4 %, warm ResNet-50 and the eight-contribution step unchanged, GoogLeNet -0.7 point;
-// 12 KB gains two more points at VGG-16 size but loses four on the warm step; 8 per compute unit
-// loses everywhere except VGG-16.  The automatic setting is therefore 16 per compute unit.
-// `which`: MC_OPT_LDS_CAP_UPDATE or MC_OPT_LDS_CAP_PACK (copy-shaped kernels only lose with a cap:
-// default none); `threads` per workgroup of the launch.
+// VGG-16 size, +2-3 % warm.  How few wavefronts a real kernel tolerates depends on how long each
+// one sits on lookups before its first load (two batches of scalar loads in the fused step, one in
+// reduce_update) and on where the traffic comes from, so the automatic setting of the update
+// kernels (update_lds_reservation) goes by the cache regime of the call, measured on the fused step:
+//   weights and momentum expected in the memory-side cache (resident policy, state that fits):
+//     16 per compute unit (10 KB per 64 threads); 12 loses 3 points there, 8 loses 7;
+//   streamed state that would fit (a cold step): 12 per compute unit (13 KB), +1 point over 16;
+//   state larger than the cache (VGG-16): 8 per compute unit (20 KB), +6-7 points over 16.
+// lds_reservation serves the copy-shaped kernels (MC_OPT_LDS_CAP_PACK; they only lose with a cap:
+// default none) and returns an explicit MC_OPT_LDS_CAP_UPDATE setting as it is; `threads` per
+// workgroup of the launch.
 unsigned lds_reservation(int which, int threads);
+unsigned update_lds_reservation(const mc_layout* L, int threads, bool stream_state);
 
 // Cache treatment of weights and momentum for a call on layout L: `policy` is the caller's
 // MC_STATE_* value (MC_STATE_DEFAULT defers to MC_OPT_STATE_POLICY).  The library cannot know

@@ -50,6 +50,21 @@ unsigned lds_reservation(int which, int threads) {
     return unsigned(v);
 }
 
+unsigned update_lds_reservation(const mc_layout* L, int threads, bool stream_state) {
+    const int v = g_lds_cap_update.load(std::memory_order_relaxed);
+    if (v >= 0) return unsigned(v);
+    // automatic.  The more of a step's traffic comes from HBM itself, the fewer wavefronts it wants:
+    // weights and momentum expected in the memory-side cache: 16 per compute unit; streamed state
+    // (nothing cached): 12; state larger than the cache: 8.
+    int per_wave = 10240;
+    if (L->N * 8 > kMemorySideCacheBytes)
+        per_wave = 20480;
+    else if (stream_state)
+        per_wave = 13312;
+    const int bytes = per_wave * (threads / 64);
+    return unsigned(bytes < 65536 ? bytes : 65536);   // (64 KB is the most a launch may ask for)
+}
+
 bool stream_state(const mc_layout* L, int policy) {
     (void)L;
     if (policy == MC_STATE_DEFAULT) policy = g_state_policy.load(std::memory_order_relaxed);

@@ -52,6 +52,8 @@ struct RuArgs {
     float* w;                       // unused when no segment updates
     float* v;
     mc::UpdateParams up;
+    uint32_t lds_per_wave;              // host only: dynamic LDS reserved by a launch of 64-thread workgroups
+    uint32_t lds_per_4waves;            //            ... of 256-thread workgroups (an occupancy cap, nothing is stored there)
 };
 
 // What a launch does with the sum.
@@ -117,10 +119,67 @@ __global__ __launch_bounds__(THREADS) void reduce_update_kernel(RuArgs a, int Pr
     }
 }
 
+// The launch most calls get: direct mapping, one wavefront per 256-element tile, a compile-time
+// term count shared by all colours.  The scalars a tile needs first are leading kernel arguments,
+// which arrive in registers when the wavefront starts (kernel-argument preload); the colour's P
+// pointers and the hyper-parameters are then fetched from the argument block in ONE batch, and the
+// tile's loads follow.  (The general kernel above reaches its first load after six dependent
+// argument fetches, because every branch on the way defers the fetches behind it.)
+// flip: index of the last tile when the launch walks backwards, -1 otherwise.
+template <int P, int MODE, bool SS>
+__global__ __launch_bounds__(64) void reduce_update_direct_kernel(float* g, float* w, float* v, int32_t tiles_per_colour,
+                                                                  uint32_t first_tile, int32_t flip, int64_t range_hi,
+                                                                  RuArgs a) {
+    static_assert(P > 0 && MODE != kPerSegment, "uniform launches with a compile-time term count");
+    constexpr int64_t kTile = MC_COLOUR_ALIGN_ELEMS;
+    const int blk = flip >= 0 ? flip - int(blockIdx.x) : int(blockIdx.x);
+    const uint32_t t = first_tile + uint32_t(blk);
+    const int s = int(t / uint32_t(tiles_per_colour));
+    const float* xp[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) xp[q] = a.x[s * P + q];
+    const mc::UpdateParams up = a.up;
+    __builtin_amdgcn_sched_barrier(0);
+    const mc::Hyper hp = mc::resolve(up);
+    const int64_t base = int64_t(t) * kTile;
+    const int64_t colour_end = int64_t(s + 1) * tiles_per_colour * kTile;
+    const int64_t hi = colour_end < range_hi ? colour_end : range_hi;
+    mc::ru_tile<P, 1, 64, MODE != kUpdateOnly, MODE != kSumOnly, SS>(xp, P, base, hi, g, w, v, hp);
+}
+
+template <int P>
+void launch_direct_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a) {
+    const dim3 grid(blocks), block(64);
+    const int32_t flip = a.reverse ? int32_t(blocks) - 1 : -1;
+#define MC_RU_LAUNCH(MODE, SS)                                                                                  \
+    hipLaunchKernelGGL((reduce_update_direct_kernel<P, MODE, SS>), grid, block,                                    \
+                       a.lds_per_wave, s, a.g, a.w, a.v, a.tiles_per_colour, a.first_tile, \
+                       flip, a.range_hi, a)
+    switch (mode) {
+        case kSumOnly: MC_RU_LAUNCH(kSumOnly, false); break;
+        case kUpdateAndG: if (ss) MC_RU_LAUNCH(kUpdateAndG, true); else MC_RU_LAUNCH(kUpdateAndG, false); break;
+        default: if (ss) MC_RU_LAUNCH(kUpdateOnly, true); else MC_RU_LAUNCH(kUpdateOnly, false); break;
+    }
+#undef MC_RU_LAUNCH
+}
+
+void launch_direct(int P, int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a) {
+    switch (P) {
+        case 1: launch_direct_mode<1>(mode, ss, blocks, s, a); break;
+        case 2: launch_direct_mode<2>(mode, ss, blocks, s, a); break;
+        case 3: launch_direct_mode<3>(mode, ss, blocks, s, a); break;
+        case 4: launch_direct_mode<4>(mode, ss, blocks, s, a); break;
+        case 5: launch_direct_mode<5>(mode, ss, blocks, s, a); break;
+        case 6: launch_direct_mode<6>(mode, ss, blocks, s, a); break;
+        case 7: launch_direct_mode<7>(mode, ss, blocks, s, a); break;
+        default: launch_direct_mode<8>(mode, ss, blocks, s, a); break;
+    }
+}
+
 template <int P, int U, int T>
 void launch_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const RuArgs& a, int Prt) {
     const dim3 grid(blocks), block(T);
-#define MC_RU_LAUNCH(MODE, SS) hipLaunchKernelGGL((reduce_update_kernel<P, U, T, MODE, SS>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, T), s, a, Prt)
+#define MC_RU_LAUNCH(MODE, SS) hipLaunchKernelGGL((reduce_update_kernel<P, U, T, MODE, SS>), grid, block, (T == 64 ? a.lds_per_wave : a.lds_per_4waves), s, a, Prt)
     switch (mode) {
         case kSumOnly: MC_RU_LAUNCH(kSumOnly, false); break;   // state is not touched: one policy
         case kUpdateAndG: if (ss) MC_RU_LAUNCH(kUpdateAndG, true); else MC_RU_LAUNCH(kUpdateAndG, false); break;
@@ -156,9 +215,9 @@ void launch(int P, mc::Shape shape, int mode, bool ss, unsigned blocks, hipStrea
 void launch_per_segment(bool ss, unsigned blocks, hipStream_t s, const RuArgs& a) {
     const dim3 grid(blocks), block(64);
     if (ss)
-        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, true>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
+        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, true>), grid, block, a.lds_per_wave, s, a, 0);
     else
-        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, false>), grid, block, mc::lds_reservation(MC_OPT_LDS_CAP_UPDATE, 64), s, a, 0);
+        hipLaunchKernelGGL((reduce_update_kernel<0, 1, 64, kPerSegment, false>), grid, block, a.lds_per_wave, s, a, 0);
 }
 
 // Shared by every entry point.  n_terms / do_update are null for the uniform call (every
@@ -214,6 +273,8 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     const bool whole = !n_terms && r_lo == 0 && r_hi == L->N;
     a.reverse = mc::sweep_reversed(L, whole ? plan.sweep : (plan.sweep == MC_SWEEP_AUTO ? MC_SWEEP_FORWARD : plan.sweep), ss) ? 1 : 0;
     a.xcd_run = mc::option(MC_OPT_XCD_RUN);
+    a.lds_per_wave = mc::update_lds_reservation(L, 64, ss);
+    a.lds_per_4waves = mc::update_lds_reservation(L, 256, ss);
     a.g = static_cast<float*>(grad_out);
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);
@@ -260,7 +321,10 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
             launch_per_segment(ss, unsigned(tiles_total), s, a);
         } else {
             const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
-            launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);
+            if (terms(first_active) <= 8 && a.xcd_run < 2)   // (a run of tiles per die is the general kernel's)
+                launch_direct(terms(first_active), mode, ss, unsigned(tiles_total), s, a);
+            else
+                launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);
         }
         MC_HIP_TRY(hipGetLastError());
         return MC_OK;

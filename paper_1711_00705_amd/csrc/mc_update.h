@@ -1,6 +1,6 @@
 // The SGD step of one element, shared by the reduce_update and fused_step kernels.
 //
-// Section 3, Algorithm 1 ends with "perform SGD"; the paper gives no formula.  Implemented:
+// Section 3, Algorithm 1 ends with an SGD step on every GPU; the paper gives no formula.  Implemented:
 // heavy-ball momentum with L2 decay folded into the gradient,
 //     d = g + wd*w;  v' = mu*v + d;  w' = w - lr*v'
 // and, with the Nesterov flag (the look-ahead form used by the Torch ResNet recipe the paper
