@@ -106,7 +106,7 @@ def parse():
                     help="what the default state policy means (0 = the library's default, 1 resident, 2 streaming)")
     ap.add_argument("--state-store-sc1", type=int, default=-1, choices=[-1, 0, 1])
     ap.add_argument("--alternate-sweep", type=int, default=-1, choices=[-1, 0, 1])
-    ap.add_argument("--direct-tiles", type=int, default=-1, choices=[-1, 0, 1])
+    ap.add_argument("--direct-tiles", type=int, default=-1, choices=[-1, 0, 1, 2])
     ap.add_argument("--lds-cap-update", type=int, default=-2)
     ap.add_argument("--lds-cap-pack", type=int, default=-2)
     ap.add_argument("--xcd-run", type=int, default=-1)

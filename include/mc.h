@@ -90,6 +90,15 @@ int mc_layout_total(const mc_layout* L, int64_t* N);
 int mc_layout_counts(const mc_layout* L, int32_t* n_tensors, int32_t* k_colours);
 int mc_layout_tensor_offsets(const mc_layout* L, int64_t* off);
 int mc_layout_colour_bounds(const mc_layout* L, int64_t* b);
+/* The work items of mc_fused_step: inside colour c, tensor t is cut into runs of 256 elements counted
+ * from the tensor's own first element (so that a run's accesses to the per-layer tensors start on a
+ * 1 KiB boundary of the tensor, whatever its flat offset); a run cut by a colour bound or by the
+ * tensor's end is shorter.  Every colour owns *units_per_colour slots.  unit_tensor (k_colours x
+ * units_per_colour entries, or NULL): the tensor of each slot, -1 for an unused one.  unit_first
+ * (n_tensors + k_colours entries, or NULL): at c + t, the index within colour c of the first run of
+ * tensor t.  *units_per_colour is 0 for layouts without this table (more than 32 colours, an empty
+ * payload), which mc_fused_step serves with flat 256-element tiles instead. */
+int mc_layout_units(const mc_layout* L, int32_t* units_per_colour, int32_t* unit_tensor, int32_t* unit_first);
 
 /* ---- a2 / a5: pack and unpack ------------------------------------------------------
  * The payload handed to the Allreduce is ONE flat buffer (Section 4.2; Section 5.1 quotes
@@ -402,9 +411,11 @@ enum {
     MC_OPT_XCD_RUN_PACK = 7,       /* the same for mc_pack / mc_pack_set; -1 (default) = chosen from the
                                       payload size */
     MC_OPT_XCD_RUN_UNPACK = 8,     /* the same for mc_unpack / mc_unpack_set */
-    MC_OPT_DIRECT_TILES = 9,       /* 0 / 1 (default 1): launches with 256-element tiles map a workgroup
-                                      to its colour by dividing the tile index by the chunk length
-                                      instead of searching a per-launch table */
+    MC_OPT_DIRECT_TILES = 9,       /* how a workgroup finds its work.  1 (default): reduce_update divides
+                                      the tile index by the chunk length to get the colour, fused_step
+                                      walks the layout's tensor-aligned units (mc_layout_units);
+                                      2: fused_step uses flat 256-element tiles like reduce_update;
+                                      0: both search a per-launch table of colour segments */
     MC_OPT_LDS_CAP_UPDATE = 10,    /* bytes of unused LDS reserved per workgroup of reduce_update and
                                       fused_step (0..65536), which caps the workgroups resident per
                                       compute unit and so the number of loads in flight; -1 (default)

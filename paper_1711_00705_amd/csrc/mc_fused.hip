@@ -52,6 +52,7 @@ struct FusedArgs {
     float* g;                           // flat payload, may be null
     const int64_t* off;                 // n+1 flat offsets
     const int32_t* first_tensor;        // lookup: first tensor per kLookupElems flat elements
+    int64_t chunk;                      // unit launches: colour chunk length
     mc::UpdateParams up;
     uint32_t lds_per_wave;              // host only: dynamic LDS reserved by a launch of 64-thread workgroups
     uint32_t lds_per_4waves;            //            ... of 256-thread workgroups (an occupancy cap, nothing is stored there)
@@ -522,6 +523,193 @@ __global__ __launch_bounds__(64) void fused_direct_kernel(const int32_t* __restr
     fused_tile<P, 1, 64, HAS_G, UPDATE, SS>(ta, xs, P, base, end, t0, t0_bounds.x, t0_bounds.y, xb, wb, vb, hp);
 }
 
+// A unit that is not a whole, aligned 256-element run: the end of a tensor, a run cut by a colour
+// bound, or operands that are not 16-byte aligned.  Lanes whose four elements all lie inside
+// [e_lo, e_hi) use 128-bit accesses when the operands allow it, the rest go element by element.
+template <int P, bool HAS_G, bool UPDATE, bool SS>
+__device__ __forceinline__ void partial_unit(const float* const* const* xs, const float* const* xb, float* wb, float* vb,
+                                             float* const* w, float* const* v, float* g, int32_t t, int64_t rel,
+                                             int64_t blk_lo, int64_t e_lo, int64_t e_hi, bool operands_aligned,
+                                             const mc::Hyper& hp) {
+    const int64_t e = blk_lo + int64_t(threadIdx.x) * 4;   // flat index of the lane's first element
+    const int64_t r = rel + int64_t(threadIdx.x) * 4;      // the same element inside tensor t
+    if (operands_aligned && e >= e_lo && e + 4 <= e_hi) {
+        float4 acc = load4<true>(xb[0] + r);
+#pragma unroll
+        for (int q = 1; q < P; ++q) {
+            const float4 x = load4<true>(xb[q] + r);
+            acc.x = acc.x + x.x;
+            acc.y = acc.y + x.y;
+            acc.z = acc.z + x.z;
+            acc.w = acc.w + x.w;
+        }
+        if (HAS_G) {
+            if ((blk_lo & 3) == 0) {
+                store4<true>(g + e, acc);
+            } else {
+                st1(g + e + 0, acc.x);
+                st1(g + e + 1, acc.y);
+                st1(g + e + 2, acc.z);
+                st1(g + e + 3, acc.w);
+            }
+        }
+        if (UPDATE) {
+            float4 wq = mc::load_state<SS>(wb + r);
+            float4 vq = mc::load_state<SS>(vb + r);
+            mc::sgd(acc.x, wq.x, vq.x, hp);
+            mc::sgd(acc.y, wq.y, vq.y, hp);
+            mc::sgd(acc.z, wq.z, vq.z, hp);
+            mc::sgd(acc.w, wq.w, vq.w, hp);
+            mc::store_state<SS>(wb + r, wq, hp.state_store_sc1);
+            mc::store_state<SS>(vb + r, vq, hp.state_store_sc1);
+        }
+        return;
+    }
+    for (int i = 0; i < 4; ++i) {
+        const int64_t ee = e + i;
+        if (ee >= e_lo && ee < e_hi) one_element<HAS_G, UPDATE>(xs, P, t, r + i, w, v, g, ee, hp);
+    }
+}
+
+// The fused step over tensor-aligned units (see mc_layout in mc_internal.h): one wavefront per unit.
+// A unit's tensor-side accesses start on a 1 KiB boundary of its tensor; only the flat gradient is
+// reached at the tensor's flat offset.  Lookups come in two batches, as in fused_direct_kernel:
+// (1) the slot's tensor, and from the argument block the colour's P pointer tables, the chunk length
+// and the hyper-parameters; (2) the tensor's bounds, the index of its first unit in
+// the colour, and the P + 2 operand addresses.
+// flip: index of the last slot when the launch walks backwards, -1 otherwise.
+template <int P, int MODE, bool SS>
+__global__ __launch_bounds__(64) void fused_unit_kernel(const int32_t* __restrict__ unit_tensor,
+                                                        const int32_t* __restrict__ unit_first,
+                                                        const int64_t* __restrict__ off, float* const* w,
+                                                        float* const* v, int32_t units_per_colour, int32_t flip,
+                                                        int64_t range_hi, FusedArgs a) {
+    static_assert(P > 0 && MODE != kPerSegment, "uniform launches with a compile-time term count");
+    constexpr int kUnit = MC_COLOUR_ALIGN_ELEMS;
+    constexpr bool HAS_G = MODE != kUpdateOnly, UPDATE = MODE != kSumOnly;
+    const int slot = flip >= 0 ? flip - int(blockIdx.x) : int(blockIdx.x);
+
+    // batch 1
+    const int c = int(uint32_t(slot) / uint32_t(units_per_colour));
+    const int local = slot - c * units_per_colour;
+    const float* const* const* xs = a.x + c * P;
+    const float* const* xt[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) xt[q] = xs[q];
+    const int64_t chunk = a.chunk;
+    float* const g = a.g;
+    const mc::UpdateParams up = a.up;
+    __builtin_amdgcn_sched_barrier(0);
+    const int32_t t_raw = unit_tensor[slot];
+    __builtin_amdgcn_sched_barrier(0);
+    // (A padding slot holds -1.  It leaves only after batch 2 has been issued, with tensor 0 standing in
+    // for the lookups: a branch here would push every fetch above to the far side of it.)
+    const int32_t t = t_raw < 0 ? 0 : t_raw;
+
+    // batch 2
+    typedef long long ll2 __attribute__((ext_vector_type(2)));
+    ll2 bounds;
+    __builtin_memcpy(&bounds, off + t, sizeof(bounds));
+    const int32_t first = unit_first[c + t];
+    const float* xb[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) xb[q] = xt[q][t];
+    float* wb = UPDATE ? w[t] : nullptr;
+    float* vb = UPDATE ? v[t] : nullptr;
+    __builtin_amdgcn_sched_barrier(0);
+    if (t_raw < 0) return;
+    const mc::Hyper hp = mc::resolve(up);
+
+    const int64_t c_lo = int64_t(c) * chunk;
+    const int64_t c_end = c_lo + chunk;
+    const int64_t c_hi = c_end < range_hi ? c_end : range_hi;
+    const int64_t lo = c_lo > bounds.x ? c_lo : bounds.x;      // the tensor's part in this colour
+    const int64_t hi = c_hi < bounds.y ? c_hi : bounds.y;
+    const int64_t j = ((lo - bounds.x) >> 8) + (local - first);
+    static_assert(kUnit == 256, "the shift above");
+    const int64_t rel = j * kUnit;                             // first element of the run, inside the tensor
+    const int64_t blk_lo = bounds.x + rel;                     // ... and in the flat payload
+    const int64_t e_lo = blk_lo > lo ? blk_lo : lo;
+    const int64_t e_hi = blk_lo + kUnit < hi ? blk_lo + kUnit : hi;
+    uintptr_t low_bits = 0;
+#pragma unroll
+    for (int q = 0; q < P; ++q) low_bits |= reinterpret_cast<uintptr_t>(xb[q]);
+    if (UPDATE) low_bits |= reinterpret_cast<uintptr_t>(wb) | reinterpret_cast<uintptr_t>(vb);
+    const bool aligned = (low_bits & 15) == 0;
+    const bool whole = (e_lo == blk_lo) & (e_hi == blk_lo + kUnit) & aligned;
+    if (!whole) {
+        partial_unit<P, HAS_G, UPDATE, SS>(xs, xb, wb, vb, w, v, g, t, rel, blk_lo, e_lo, e_hi, aligned, hp);
+        return;
+    }
+    // A whole run: every load of the unit is issued before the first add.
+    const int64_t r = rel + int64_t(threadIdx.x) * 4;
+    float4 term[P], wq, vq;
+#pragma unroll
+    for (int q = 0; q < P; ++q) term[q] = load4<true>(xb[q] + r);
+    if (UPDATE) {
+        wq = mc::load_state<SS>(wb + r);
+        vq = mc::load_state<SS>(vb + r);
+    }
+    float4 acc = term[0];
+#pragma unroll
+    for (int q = 1; q < P; ++q) {
+        acc.x = acc.x + term[q].x;
+        acc.y = acc.y + term[q].y;
+        acc.z = acc.z + term[q].z;
+        acc.w = acc.w + term[q].w;
+    }
+    if (HAS_G) {
+        float* gq = g + blk_lo + int64_t(threadIdx.x) * 4;
+        if ((blk_lo & 3) == 0) {
+            store4<true>(gq, acc);
+        } else {   // the tensor's flat offset is not a multiple of four elements: word by word
+            st1(gq + 0, acc.x);
+            st1(gq + 1, acc.y);
+            st1(gq + 2, acc.z);
+            st1(gq + 3, acc.w);
+        }
+    }
+    if (UPDATE) {
+        mc::sgd(acc.x, wq.x, vq.x, hp);
+        mc::sgd(acc.y, wq.y, vq.y, hp);
+        mc::sgd(acc.z, wq.z, vq.z, hp);
+        mc::sgd(acc.w, wq.w, vq.w, hp);
+        mc::store_state<SS>(wb + r, wq, hp.state_store_sc1);
+        mc::store_state<SS>(vb + r, vq, hp.state_store_sc1);
+    }
+}
+
+template <int P>
+void launch_unit_mode(int mode, bool ss, hipStream_t s, const FusedArgs& a, const mc::DeviceTables* dt,
+                      int32_t units_per_colour, int32_t k) {
+    const unsigned blocks = unsigned(units_per_colour) * unsigned(k);
+    const dim3 grid(blocks), block(64);
+    const int32_t flip = a.reverse ? int32_t(blocks) - 1 : -1;
+#define MC_FUSED_LAUNCH(MODE, SS)                                                                               \
+    hipLaunchKernelGGL((fused_unit_kernel<P, MODE, SS>), grid, block, a.lds_per_wave, s, dt->unit_tensor,          \
+                       dt->unit_first, a.off, a.w, a.v, units_per_colour, flip, a.range_hi, a)
+    switch (mode) {
+        case kSumOnly: MC_FUSED_LAUNCH(kSumOnly, false); break;
+        case kUpdateAndG: if (ss) MC_FUSED_LAUNCH(kUpdateAndG, true); else MC_FUSED_LAUNCH(kUpdateAndG, false); break;
+        default: if (ss) MC_FUSED_LAUNCH(kUpdateOnly, true); else MC_FUSED_LAUNCH(kUpdateOnly, false); break;
+    }
+#undef MC_FUSED_LAUNCH
+}
+
+void launch_units(int P, int mode, bool ss, hipStream_t s, const FusedArgs& a, const mc::DeviceTables* dt,
+                  int32_t units_per_colour, int32_t k) {
+    switch (P) {
+        case 1: launch_unit_mode<1>(mode, ss, s, a, dt, units_per_colour, k); break;
+        case 2: launch_unit_mode<2>(mode, ss, s, a, dt, units_per_colour, k); break;
+        case 3: launch_unit_mode<3>(mode, ss, s, a, dt, units_per_colour, k); break;
+        case 4: launch_unit_mode<4>(mode, ss, s, a, dt, units_per_colour, k); break;
+        case 5: launch_unit_mode<5>(mode, ss, s, a, dt, units_per_colour, k); break;
+        case 6: launch_unit_mode<6>(mode, ss, s, a, dt, units_per_colour, k); break;
+        case 7: launch_unit_mode<7>(mode, ss, s, a, dt, units_per_colour, k); break;
+        default: launch_unit_mode<8>(mode, ss, s, a, dt, units_per_colour, k); break;
+    }
+}
+
 template <int P>
 void launch_direct_mode(int mode, bool ss, unsigned blocks, hipStream_t s, const FusedArgs& a) {
     const dim3 grid(blocks), block(64);
@@ -767,6 +955,7 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
 
     a.tiles_per_colour = 0;
     a.range_hi = L->N;
+    a.chunk = 0;
     auto pointer_list = [&](int32_t c, int slot) {
         for (int32_t q = 0; q < terms(c); ++q)
             a.x[slot + q] = reinterpret_cast<const float* const*>(contrib[order ? order[size_t(c) * P + q] : q]->d_ptrs);
@@ -794,7 +983,11 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
         int slots = 0;
         for (int32_t c = 0; c < L->k; ++c) {
             if (!per_segment) {
-                if (L->bounds[c + 1] > L->bounds[c]) pointer_list(c, c * terms(first_active));
+                // (Every colour, an empty one too: a padding slot of the unit kernel reads its colour's
+                // tables before it leaves.)
+                for (int32_t q = 0; q < terms(first_active); ++q)
+                    a.x[c * terms(first_active) + q] =
+                        reinterpret_cast<const float* const*>(contrib[order ? order[size_t(c) * P + q] : q]->d_ptrs);
             } else if (active(c)) {
                 a.seg_info[c] = uint32_t(slots) | (uint32_t(terms(c)) << 16) | (updates(c) ? (1u << 24) : 0u);
                 pointer_list(c, slots);
@@ -805,7 +998,11 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             launch_per_segment(ss, unsigned(tiles_total), s, a);
         } else {
             const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
-            if (terms(first_active) <= 8 && a.xcd_run < 2)   // (a run of tiles per die is the general kernel's)
+            const bool few = terms(first_active) <= 8 && a.xcd_run < 2;   // (a run of tiles per die is the general kernel's)
+            if (few && dt->unit_tensor && mc::option(MC_OPT_DIRECT_TILES) == 1) {
+                a.chunk = L->chunk;
+                launch_units(terms(first_active), mode, ss, s, a, dt, L->units_per_colour, L->k);
+            } else if (few)
                 launch_direct(terms(first_active), mode, ss, unsigned(tiles_total), s, a);
             else
                 launch(terms(first_active), shape, mode, ss, unsigned(tiles_total), s, a);

@@ -31,6 +31,8 @@ struct DeviceTables {
     bool ready = false;
     int64_t* off = nullptr;         // n+1 flat offsets
     int32_t* tile_first = nullptr;  // per kLookupElems flat elements: first tensor that may intersect them
+    int32_t* unit_tensor = nullptr; // per unit slot: its tensor, -1 for padding (null when the layout has no unit table)
+    int32_t* unit_first = nullptr;  // at c + t: index in colour c of the first unit of tensor t
 };
 
 }  // namespace mc
@@ -43,6 +45,20 @@ struct mc_layout {
     std::vector<int64_t> off;         // n+1
     std::vector<int64_t> bounds;      // k+1
     std::vector<int32_t> tile_first;  // ceil(N / kLookupElems) + 1
+    // Tensor-aligned units (the fused step's work items): inside colour c, tensor t is cut into
+    // runs of 256 elements counted from the TENSOR's first element, so that a unit's accesses to
+    // the per-layer tensors start on a 1 KiB boundary of the tensor whatever its flat offset is
+    // (a tile grid laid over the flat index instead leaves every tensor-side access of a tile
+    // straddling cache lines, shared with the neighbouring tile, once an earlier tensor's length
+    // is not a multiple of 32).  A run cut by a colour bound or by the tensor's end is a shorter
+    // unit.  Every colour owns units_per_colour slots (the largest count; unused slots hold -1),
+    // so a slot's colour is its index divided by that number.  Empty when k > 32 or the slot count
+    // does not fit 31 bits.
+    std::vector<int32_t> unit_tensor;  // k * units_per_colour
+    // Index in colour c of the first unit of tensor t, at position c + t (colours and tensors both
+    // advance along the payload, so c + t names the pair uniquely): n + k entries.
+    std::vector<int32_t> unit_first;
+    int32_t units_per_colour = 0;
     // Parity of the next whole-payload update call with automatic sweep direction (see
     // sweep_reversed()): the one member that changes after prepare; it never affects a result.
     mutable std::atomic<uint32_t> sweep{0};

@@ -1,5 +1,6 @@
 // Host side of the layout: flat offsets, colour bounds, pack-tile table, options, errors.
 // Nothing in this file touches the GPU.
+#include <algorithm>
 #include <atomic>
 #include <new>
 
@@ -144,11 +145,59 @@ int mc_layout_create(const int64_t* numel, int32_t n_tensors, int32_t k_colours,
             while (t < n_tensors && L->off[t + 1] <= first) ++t;
             L->tile_first[j] = t;  // == n_tensors only when first >= N
         }
+
+        // Tensor-aligned units of each colour (see mc_internal.h).
+        if (k_colours <= 32 && total > 0) {
+            const int64_t u = MC_COLOUR_ALIGN_ELEMS;
+            std::vector<int32_t> t_lo(size_t(k_colours), 0), t_hi(size_t(k_colours), -1);
+            std::vector<int64_t> count(size_t(k_colours), 0);
+            int64_t most = 0;
+            int32_t tt = 0;
+            for (int32_t c = 0; c < k_colours; ++c) {
+                const int64_t lo_c = L->bounds[c], hi_c = L->bounds[c + 1];
+                if (hi_c <= lo_c) continue;
+                while (L->off[tt + 1] <= lo_c) ++tt;        // lo_c < N == off[n]
+                t_lo[c] = tt;
+                int32_t te = tt;
+                for (;; ++te) {
+                    const int64_t lo = std::max(lo_c, L->off[te]), hi = std::min(hi_c, L->off[te + 1]);
+                    if (hi > lo) count[c] += (hi - L->off[te] + u - 1) / u - (lo - L->off[te]) / u;
+                    if (L->off[te + 1] >= hi_c) break;
+                }
+                t_hi[c] = te;
+                most = std::max(most, count[c]);
+            }
+            if (most * k_colours < 0x7fffffff) {
+                L->units_per_colour = int32_t(most);
+                L->unit_tensor.assign(size_t(most) * size_t(k_colours), -1);
+                L->unit_first.assign(size_t(n_tensors) + size_t(k_colours), 0);
+                for (int32_t c = 0; c < k_colours; ++c) {
+                    const int64_t lo_c = L->bounds[c], hi_c = L->bounds[c + 1];
+                    int64_t local = 0;
+                    for (int32_t te = t_lo[c]; te <= t_hi[c]; ++te) {
+                        L->unit_first[size_t(c) + size_t(te)] = int32_t(local);
+                        const int64_t lo = std::max(lo_c, L->off[te]), hi = std::min(hi_c, L->off[te + 1]);
+                        if (hi <= lo) continue;
+                        const int64_t nu = (hi - L->off[te] + u - 1) / u - (lo - L->off[te]) / u;
+                        for (int64_t j = 0; j < nu; ++j) L->unit_tensor[size_t(c) * size_t(most) + size_t(local + j)] = te;
+                        local += nu;
+                    }
+                }
+            }
+        }
     } catch (const std::bad_alloc&) {
         delete L;
         return MC_ERR_ALLOC;
     }
     *out = L;
+    return MC_OK;
+}
+
+int mc_layout_units(const mc_layout* L, int32_t* units_per_colour, int32_t* unit_tensor, int32_t* unit_first) {
+    if (!L || !units_per_colour) return MC_ERR_INVALID_ARG;
+    *units_per_colour = L->unit_tensor.empty() ? 0 : L->units_per_colour;
+    if (unit_tensor) std::copy(L->unit_tensor.begin(), L->unit_tensor.end(), unit_tensor);
+    if (unit_first) std::copy(L->unit_first.begin(), L->unit_first.end(), unit_first);
     return MC_OK;
 }
 
@@ -235,7 +284,7 @@ int mc_set_option(int option, int value) {
             g_lds_cap_pack.store(value, std::memory_order_relaxed);
             return MC_OK;
         case MC_OPT_DIRECT_TILES:
-            if (value != 0 && value != 1) return MC_ERR_INVALID_ARG;
+            if (value < 0 || value > 2) return MC_ERR_INVALID_ARG;
             g_direct_tiles.store(value, std::memory_order_relaxed);
             return MC_OK;
         default:

@@ -385,8 +385,27 @@ int device_tables(mc_layout* L, const DeviceTables** out) {
             (void)hipFree(tf);
             return hip_fail(e);
         }
+        int32_t *ut = nullptr, *uf = nullptr;
+        if (!L->unit_tensor.empty()) {
+            const size_t ut_bytes = L->unit_tensor.size() * sizeof(int32_t);
+            const size_t uf_bytes = std::max<size_t>(L->unit_first.size(), 1) * sizeof(int32_t);
+            e = hipMalloc(reinterpret_cast<void**>(&ut), ut_bytes);
+            if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&uf), uf_bytes);
+            if (e == hipSuccess) e = hipMemcpy(ut, L->unit_tensor.data(), ut_bytes, hipMemcpyHostToDevice);
+            if (e == hipSuccess && !L->unit_first.empty())
+                e = hipMemcpy(uf, L->unit_first.data(), L->unit_first.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+            if (e != hipSuccess) {
+                (void)hipFree(off);
+                (void)hipFree(tf);
+                (void)hipFree(ut);
+                (void)hipFree(uf);
+                return hip_fail(e);
+            }
+        }
         d.off = off;
         d.tile_first = tf;
+        d.unit_tensor = ut;
+        d.unit_first = uf;
         d.ready = true;
     }
     *out = &d;
@@ -418,6 +437,8 @@ int mc_layout_destroy(mc_layout* L) {
             hipError_t e = hipSetDevice(d);
             if (e == hipSuccess) e = hipFree(t.off);
             if (e == hipSuccess) e = hipFree(t.tile_first);
+            if (e == hipSuccess && t.unit_tensor) e = hipFree(t.unit_tensor);
+            if (e == hipSuccess && t.unit_first) e = hipFree(t.unit_first);
             if (e != hipSuccess) rc = mc::hip_fail(e);
             t.ready = false;
         }

@@ -57,6 +57,7 @@ SIGNATURES = {
     "mc_layout_counts": (ctypes.c_int, [_vp, _i32p, _i32p]),
     "mc_layout_tensor_offsets": (ctypes.c_int, [_vp, _i64p]),
     "mc_layout_colour_bounds": (ctypes.c_int, [_vp, _i64p]),
+    "mc_layout_units": (ctypes.c_int, [_vp, _i32p, _i32p, _i32p]),
     "mc_pack": (ctypes.c_int, [_vp, _vpp, _vp, _vp]),
     "mc_unpack": (ctypes.c_int, [_vp, _vp, _vpp, _vp]),
     "mc_pack_noalloc": (ctypes.c_int, [_vp, _vpp, _vp, _vp]),
@@ -203,6 +204,18 @@ class Layout:
         b = np.empty(self.k + 1, dtype=np.int64)
         _check(lib.mc_layout_colour_bounds(self._h, b.ctypes.data_as(_i64p)), "mc_layout_colour_bounds")
         return b
+
+    def units(self):
+        """(units_per_colour, unit_tensor[k, units_per_colour], unit_first[n + k]); (0, None, None) without a table."""
+        upc = ctypes.c_int32()
+        _check(lib.mc_layout_units(self._h, ctypes.byref(upc), None, None), "mc_layout_units")
+        if upc.value == 0:
+            return 0, None, None
+        ut = np.empty(self.k * upc.value, dtype=np.int32)
+        uf = np.empty(self.n + self.k, dtype=np.int32)
+        _check(lib.mc_layout_units(self._h, ctypes.byref(upc), ut.ctypes.data_as(_i32p), uf.ctypes.data_as(_i32p)),
+               "mc_layout_units")
+        return upc.value, ut.reshape(self.k, upc.value), uf
 
     def prepare(self) -> None:
         _check(lib.mc_layout_prepare(self._h), "mc_layout_prepare")

@@ -185,7 +185,7 @@ def test_options():
                            (mc.OPT_XCD_RUN, (0, 1, 8, 64), (-1, 65)),
                            (mc.OPT_XCD_RUN_PACK, (-1, 0, 16, 64), (-2, 65)),
                            (mc.OPT_XCD_RUN_UNPACK, (-1, 0, 16, 64), (-2, 65)),
-                           (mc.OPT_DIRECT_TILES, (0, 1), (-1, 2)),
+                           (mc.OPT_DIRECT_TILES, (0, 1, 2), (-1, 3)),
                            (mc.OPT_LDS_CAP_UPDATE, (-1, 0, 20480, 65536), (-2, 65537)),
                            (mc.OPT_LDS_CAP_PACK, (-1, 0, 20480, 65536), (-2, 65537))):
         keep = mc.get_option(opt)

@@ -50,7 +50,7 @@ def _case(seed):
     opts[mc.OPT_XCD_RUN] = int(rng.choice([0, 0, 2, 3, 8, 64]))
     opts[mc.OPT_XCD_RUN_PACK] = int(rng.choice([-1, 0, 2, 16, 64]))
     opts[mc.OPT_XCD_RUN_UNPACK] = int(rng.choice([-1, 0, 3, 16]))
-    opts[mc.OPT_DIRECT_TILES] = int(rng.integers(0, 2))
+    opts[mc.OPT_DIRECT_TILES] = int(rng.integers(0, 3))
     opts[mc.OPT_LDS_CAP_UPDATE] = int(rng.choice([-1, 0, 4096, 40960]))
     opts[mc.OPT_LDS_CAP_PACK] = int(rng.choice([-1, 0, 8192]))
     hyper = [float(x) for x in (rng.choice([0.1, 0.01, 0.5]), rng.choice([0.9, 0.0, 0.5]), rng.choice([1e-4, 0.0, 5e-4]))]

@@ -1,0 +1,85 @@
+"""The fused step's work items (mc_layout_units): every element of the payload must belong to exactly
+one unit, inside its tensor and inside its colour, and every unit must be a run of at most 256
+elements that starts on a multiple of 256 counted from its tensor's first element (or at a colour
+bound).  The ranges are rebuilt here the way the kernel derives them from the two tables."""
+import numpy as np
+import pytest
+
+from paper_1711_00705_amd import mc
+from paper_1711_00705_amd import workloads as wl
+
+A = 256
+
+
+def unit_ranges(L):
+    """[(colour, tensor, flat_lo, flat_hi)] of every used slot, computed as the kernel does."""
+    upc, ut, uf = L.units()
+    assert upc > 0
+    off, b = L.tensor_offsets(), L.colour_bounds()
+    chunk = int(b[1] - b[0]) if L.k > 1 and b[1] < L.N else None
+    out = []
+    for c in range(L.k):
+        for local in range(upc):
+            t = int(ut[c, local])
+            if t < 0:
+                continue
+            assert b[c + 1] > b[c], "an empty colour has no units"
+            if chunk is not None:
+                assert b[c] == c * chunk, "colour bounds are multiples of the chunk length"
+            lo = max(int(b[c]), int(off[t]))
+            hi = min(int(b[c + 1]), int(off[t + 1]))
+            assert hi > lo, "a unit's tensor intersects its colour"
+            j = (lo - int(off[t])) // A + (local - int(uf[c + t]))
+            assert j >= 0
+            blk = int(off[t]) + j * A
+            e_lo, e_hi = max(blk, lo), min(blk + A, hi)
+            assert e_hi > e_lo, f"unit {c}/{local} of tensor {t} is empty"
+            out.append((c, t, e_lo, e_hi))
+    return out
+
+
+def check(sizes, k):
+    L = mc.Layout(sizes, k)
+    if L.N == 0:
+        assert L.units()[0] == 0
+        return
+    r = unit_ranges(L)
+    off, b = L.tensor_offsets(), L.colour_bounds()
+    cover = np.zeros(L.N, dtype=np.int32)
+    for c, t, lo, hi in r:
+        assert off[t] <= lo and hi <= off[t + 1] and b[c] <= lo and hi <= b[c + 1]
+        assert hi - lo <= A
+        assert (lo - off[t]) % A == 0 or lo == b[c], "a unit starts on a tensor-relative multiple of 256 or at a colour bound"
+        cover[lo:hi] += 1
+    assert np.all(cover == 1), "every element in exactly one unit"
+    upc, ut, _ = L.units()
+    used = (ut >= 0).sum(axis=1)
+    assert used.max() == upc, "the slot count is the largest colour's"
+    for c in range(L.k):
+        assert np.all(ut[c, :used[c]] >= 0) and np.all(ut[c, used[c]:] == -1), "unused slots are at the end"
+        assert np.all(np.diff(ut[c, :used[c]]) >= 0), "units follow the payload"
+
+
+@pytest.mark.parametrize("name", ["tiny", "googlenet"])
+def test_units_of_the_workloads(name):
+    w = wl.workload(name)
+    check(w.sizes, w.k)
+
+
+def test_units_of_odd_layouts():
+    rng = np.random.default_rng(5)
+    for trial in range(60):
+        n = int(rng.integers(1, 12))
+        sizes = [int(x) for x in rng.choice([0, 1, 3, 4, 5, 255, 256, 257, 511, 1000, 1024, 4099, 70001], size=n)]
+        k = int(rng.integers(1, 9))
+        check(sizes, k)
+    check([0, 0, 7, 0], 3)
+    check([256 * 7], 7)          # colour bounds on tensor-relative multiples
+    check([100, 256 * 8, 100], 4)
+    check([1] * 50, 5)
+
+
+def test_no_table_beyond_32_colours_or_without_elements():
+    assert mc.Layout([1000] * 40, 33).units()[0] == 0
+    assert mc.Layout([0, 0], 2).units()[0] == 0
+    assert mc.Layout([1000] * 40, 32).units()[0] > 0
