@@ -77,6 +77,16 @@ def traffic_from_profile(kernel, workload, P, k):
     return traffic, os.path.relpath(path, ROOT)
 
 
+def kernel_names(mc, L, P, k):
+    """Which kernels the library launches for the uniform step under the current options."""
+    how = mc.get_option(mc.OPT_DIRECT_TILES)
+    plain = mc.get_option(mc.OPT_RU_SHAPE) != 2 and mc.get_option(mc.OPT_XCD_RUN) < 2 and P <= 8 and k <= 32
+    if not plain or how == 0:
+        return "fused_step_kernel", "reduce_update_kernel"
+    fused = "fused_unit_kernel" if how == 1 and L.units()[0] > 0 else "fused_direct_kernel"
+    return fused, "reduce_update_direct_kernel"
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -622,7 +632,8 @@ def main():
         mc.fused_step(L, tsets[i % n_sets], order, g.data_ptr(), fw_set, fv_set, cfg.lr, cfg.mu, cfg.wd, sh)
 
     fused = args.path == "fused"
-    kernel_name = "fused_step_kernel" if fused else "reduce_update_kernel"
+    fused_kernel, staged_kernel = kernel_names(mc, L, P, k)
+    kernel_name = fused_kernel if fused else staged_kernel
     kernel_bytes = 4 * (P + 5) * N        # P reads + w, v read and written + g written: same for both kernels
     staged_bytes = (8 * P + 4 * (P + 5) + 8) * N
     step_bytes = kernel_bytes if fused else staged_bytes
@@ -785,7 +796,7 @@ def main():
     }
     if cold is not None:
         c = cold["streaming"]
-        out["roofline_cold"] = {"bound": "hbm", "kernel": "fused_step_kernel", "achieved": c["GBps"],
+        out["roofline_cold"] = {"bound": "hbm", "kernel": fused_kernel, "achieved": c["GBps"],
                                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": c["frac"],
                                 "bytes_per_launch": kernel_bytes, "kernel_ms": c["kernel_ms"],
                                 "ms_per_step": c["ms_per_step"], "state_policy": "streaming",

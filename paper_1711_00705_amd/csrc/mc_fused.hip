@@ -453,9 +453,10 @@ __global__ __launch_bounds__(THREADS) void fused_step_kernel(FusedArgs a, int Pr
     }
 }
 
-// The common launch -- direct tile mapping, every colour adding the same compile-time number of
-// terms, one wavefront per 256-element tile -- with its lookups arranged in two batches, each issued
-// as a whole before any of it is waited for:
+// Flat 256-element tiles with direct tile -> colour mapping, every colour adding the same
+// compile-time number of terms, one wavefront per tile (MC_OPT_DIRECT_TILES = 2, and layouts
+// without a unit table; the default launch is fused_unit_kernel below, which shares the scheme).
+// The lookups are arranged in two batches, each issued as a whole before any of it is waited for:
 //   1. what depends only on the tile index: the tile's tensor and the colour's P pointer tables;
 //   2. what depends only on that tensor: its bounds and the P + 2 operand addresses.
 // The decision which path the tile takes is ONE expression over all of them, evaluated without
@@ -571,9 +572,12 @@ __device__ __forceinline__ void partial_unit(const float* const* const* xs, cons
     }
 }
 
-// The fused step over tensor-aligned units (see mc_layout in mc_internal.h): one wavefront per unit.
-// A unit's tensor-side accesses start on a 1 KiB boundary of its tensor; only the flat gradient is
-// reached at the tensor's flat offset.  Lookups come in two batches, as in fused_direct_kernel:
+// The default launch of the fused step: tensor-aligned units (see mc_layout in mc_internal.h), one
+// wavefront per unit.  A unit's tensor-side accesses start on a 1 KiB boundary of its tensor; only
+// the flat gradient is reached at the tensor's flat offset.  (With flat tiles, one tensor whose length
+// is not a multiple of 32 elements leaves every later tile's P + 2 tensor-side accesses straddling
+// cache lines that the neighbouring tile, on another die, fetches again: GoogLeNet's step took 4 %
+// longer for it, and a ResNet-50-sized payload split in two at an offset of 4 elements 5 %.)  Lookups come in two batches, as in fused_direct_kernel:
 // (1) the slot's tensor, and from the argument block the colour's P pointer tables, the chunk length
 // and the hyper-parameters; (2) the tensor's bounds, the index of its first unit in
 // the colour, and the P + 2 operand addresses.

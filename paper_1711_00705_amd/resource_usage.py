@@ -71,6 +71,7 @@ def main() -> None:
     print("(python -m paper_1711_00705_amd.resource_usage; flags: " + " ".join(b.HIPCC_FLAGS) + ")")
     print("Template arguments: reduce_update_kernel / fused_step_kernel <terms (0 = run-time count), vectors per")
     print("thread, threads, mode (0 sum only, 1 update + g, 2 update, 3 per segment), streamed state>;")
+    print("reduce_update_direct_kernel / fused_direct_kernel / fused_unit_kernel <terms, mode, streamed state>;")
     print("gather_scatter_kernel <unpack, stream tensors, stream flat, vectors per thread>.")
     print()
     head = ("kernel", "VGPR", "AGPR", "SGPR", "scratch B/lane", "waves/SIMD", "VGPR spill", "SGPR spill", "LDS B")

@@ -25,14 +25,14 @@ def test_measured_traffic_comes_from_the_profile_summaries():
     import bench
     digest = bench.csrc_digest()
     assert len(digest) == 16 and digest == bench.csrc_digest()
-    for kernel, wl_, P, k, algorithmic in (("fused_step_kernel", "resnet50", 4, 4, 920053152),
-                                           ("fused_step_kernel", "vgg16", 4, 4, 4980871584)):
+    for kernel, wl_, P, k, algorithmic in (("fused_unit_kernel", "resnet50", 4, 4, 920053152),
+                                           ("fused_unit_kernel", "vgg16", 4, 4, 4980871584)):
         t, src = bench.traffic_from_profile(kernel, wl_, P, k)
-        recorded = [l.split(":")[1].strip() for l in open(os.path.join(ROOT, "profiles", f"fused_step_{wl_}_P{P}_k{k}.txt"))
+        recorded = [l.split(":")[1].strip() for l in open(os.path.join(ROOT, "profiles", f"fused_unit_{wl_}_P{P}_k{k}.txt"))
                     if l.startswith("csrc_digest:")]
         if recorded and recorded[0] == digest:
             assert t is not None and 0.98 * algorithmic < t < 1.05 * algorithmic and src.startswith("profiles/")
         else:
             assert t is None and "other kernel sources" in src
-    t, src = bench.traffic_from_profile("fused_step_kernel", "no_such_workload", 4, 4)
+    t, src = bench.traffic_from_profile("fused_unit_kernel", "no_such_workload", 4, 4)
     assert t is None and "no counter profile" in src
