@@ -65,47 +65,53 @@ __device__ __forceinline__ void st4(uint32_t* p, const uint4& q) {
 // NT_T / NT_F: streaming policy for the tensor side / the flat side (non-temporal loads,
 // write-through stores).
 // V: 16-byte vectors per thread; a workgroup covers a tile of kThreads * 4 * V flat elements.
-template <bool UNPACK, bool NT_T, bool NT_F, int V>
+// TABLE: tensor addresses come from a tensor set's device table instead of the argument block (a
+// compile-time choice: a run-time one makes the compiler fetch the address with a per-lane load
+// through a selected pointer).
+template <bool UNPACK, bool NT_T, bool NT_F, int V, bool TABLE>
 __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
-    PtrBatch ptrs, void* const* __restrict__ table, const int64_t* __restrict__ off,
-    const int32_t* __restrict__ tile_first, uint32_t* flat, int32_t t0, int32_t t1, int64_t tile0,
-    int xcd_run) {
+    void* const* __restrict__ table, const int64_t* __restrict__ off, const int32_t* __restrict__ tile_first,
+    uint32_t* flat, int64_t tile0, int64_t hi, int32_t t0, int32_t xcd_run, int64_t lo, PtrBatch ptrs) {
+    // lo, hi: the launch's flat range [off[t0], off[t1]).  The scalars in front of lo are what a
+    // tile needs before its first lookup; as leading arguments they arrive in registers when the
+    // wavefront starts (kernel-argument preload).
     constexpr int64_t kTileElems = int64_t(kThreads) * 4 * V;
     static_assert(kTileElems % mc::kLookupElems == 0, "tiles start on lookup entries");
     const int64_t tile = tile0 + mc::xcd_tile(int(blockIdx.x), int(gridDim.x), xcd_run);
-    const int64_t lo = off[t0];
-    const int64_t hi = off[t1];
     const int64_t tile_base = tile * kTileElems;
     const int32_t t_tile = max(tile_first[tile_base / mc::kLookupElems], t0);
+    __builtin_amdgcn_sched_barrier(0);
 
     // Whole tile inside one tensor (and inside this launch's range) with a 16-byte aligned
     // tensor side: nearly all bytes of a CNN payload.  Everything deciding it is uniform over
-    // the workgroup, so the lookups are scalar loads, and all V loads precede the first store.
-    if (tile_base >= lo && tile_base + kTileElems <= hi) {
-        const int64_t t_lo = off[t_tile];
-        const int64_t t_hi = off[t_tile + 1];
-        if (t_lo <= tile_base && tile_base + kTileElems <= t_hi) {
-            uint32_t* tens =
-                static_cast<uint32_t*>(table ? table[t_tile] : ptrs.p[t_tile - t0]) + (tile_base - t_lo);
-            if ((reinterpret_cast<uintptr_t>(tens) & 15) == 0) {
-                uint32_t* fl = flat + tile_base;
-                uint4 q[V];
+    // the workgroup, so the lookups are scalar loads; the tensor's bounds and its address are
+    // fetched together and the decision is one expression over them (no fetch waits behind a
+    // branch), and all V loads precede the first store.
+    typedef long long ll2 __attribute__((ext_vector_type(2)));
+    ll2 bounds;
+    __builtin_memcpy(&bounds, off + t_tile, sizeof(bounds));
+    uint32_t* const t_base = static_cast<uint32_t*>(TABLE ? table[t_tile] : ptrs.p[t_tile - t0]);
+    __builtin_amdgcn_sched_barrier(0);
+    uint32_t* const tens = t_base + (tile_base - bounds.x);
+    const bool whole = (tile_base >= lo) & (tile_base + kTileElems <= hi) & (bounds.x <= tile_base) &
+                       (tile_base + kTileElems <= bounds.y) & ((reinterpret_cast<uintptr_t>(tens) & 15) == 0);
+    if (whole) {
+        uint32_t* fl = flat + tile_base;
+        uint4 q[V];
 #pragma unroll
-                for (int j = 0; j < V; ++j) {
-                    const int e = (j * kThreads + int(threadIdx.x)) * 4;
-                    q[j] = UNPACK ? ld4<NT_F>(fl + e) : ld4<NT_T>(tens + e);
-                }
-#pragma unroll
-                for (int j = 0; j < V; ++j) {
-                    const int e = (j * kThreads + int(threadIdx.x)) * 4;
-                    if (UNPACK)
-                        st4<NT_T>(tens + e, q[j]);
-                    else
-                        st4<NT_F>(fl + e, q[j]);
-                }
-                return;
-            }
+        for (int j = 0; j < V; ++j) {
+            const int e = (j * kThreads + int(threadIdx.x)) * 4;
+            q[j] = UNPACK ? ld4<NT_F>(fl + e) : ld4<NT_T>(tens + e);
         }
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const int e = (j * kThreads + int(threadIdx.x)) * 4;
+            if (UNPACK)
+                st4<NT_T>(tens + e, q[j]);
+            else
+                st4<NT_F>(fl + e, q[j]);
+        }
+        return;
     }
 
 #pragma unroll
@@ -118,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
 
         const bool one_tensor = i >= lo && i + 4 <= off[t + 1];
         if (one_tensor) {
-            uint32_t* src = static_cast<uint32_t*>(table ? table[t] : ptrs.p[t - t0]) + (i - off[t]);
+            uint32_t* src = static_cast<uint32_t*>(TABLE ? table[t] : ptrs.p[t - t0]) + (i - off[t]);
             if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
                 if (UNPACK)
                     st4<NT_T>(src, ld4<NT_F>(flat + i));
@@ -146,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void gather_scatter_kernel(
             const int64_t idx = i + e;
             if (idx < lo || idx >= hi) continue;
             while (off[t + 1] <= idx) ++t;
-            uint32_t* elem = static_cast<uint32_t*>(table ? table[t] : ptrs.p[t - t0]) + (idx - off[t]);
+            uint32_t* elem = static_cast<uint32_t*>(TABLE ? table[t] : ptrs.p[t - t0]) + (idx - off[t]);
             if (UNPACK)
                 st1(elem, ld1(flat + idx));
             else
@@ -178,14 +184,22 @@ int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch&
     int xcd_run = mc::option(UNPACK ? MC_OPT_XCD_RUN_UNPACK : MC_OPT_XCD_RUN_PACK);
     if (xcd_run < 0) xcd_run = (!UNPACK && vec == 1) ? 16 : 0;
     const unsigned lds = mc::lds_reservation(MC_OPT_LDS_CAP_PACK, kThreads);
-#define MC_GS_LAUNCH(NT_T, NT_F)                                                                       \
-    do {                                                                                               \
-        if (vec == 2)                                                                                  \
-            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 2>), grid, block, lds, s, batch, \
-                               table, dt->off, dt->tile_first, f, t0, t1, tile0, xcd_run);             \
-        else                                                                                           \
-            hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, 1>), grid, block, lds, s, batch, \
-                               table, dt->off, dt->tile_first, f, t0, t1, tile0, xcd_run);             \
+#define MC_GS_LAUNCH_V(NT_T, NT_F, V, TABLE)                                                                  \
+    hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, V, TABLE>), grid, block, lds, s, table, dt->off, \
+                       dt->tile_first, f, tile0, hi, t0, xcd_run, lo, batch)
+#define MC_GS_LAUNCH(NT_T, NT_F)                                   \
+    do {                                                           \
+        if (vec == 2) {                                            \
+            if (table)                                             \
+                MC_GS_LAUNCH_V(NT_T, NT_F, 2, true);               \
+            else                                                   \
+                MC_GS_LAUNCH_V(NT_T, NT_F, 2, false);              \
+        } else {                                                   \
+            if (table)                                             \
+                MC_GS_LAUNCH_V(NT_T, NT_F, 1, true);               \
+            else                                                   \
+                MC_GS_LAUNCH_V(NT_T, NT_F, 1, false);              \
+        }                                                          \
     } while (0)
     switch (nt & 3) {
         case 0: MC_GS_LAUNCH(false, false); break;
@@ -193,6 +207,7 @@ int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch&
         case 2: MC_GS_LAUNCH(false, true); break;
         default: MC_GS_LAUNCH(true, true); break;
     }
+#undef MC_GS_LAUNCH_V
 #undef MC_GS_LAUNCH
     MC_HIP_TRY(hipGetLastError());
     return MC_OK;
