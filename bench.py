@@ -275,6 +275,75 @@ def cold_pass(H, I, order, steps, warmup):
     return out, states, gs
 
 
+def replayed_pair(H, I, order, g, st, cfg, warmup, steps):
+    """The same back-to-back steps from two captured graphs, one per contribution set and walking
+    direction (a graph replays the direction it captured, so a caller whose state exceeds the cache
+    captures one of each and alternates them)."""
+    mc, torch = H.mc, H.torch
+    graphs = []
+    for j, sweep in enumerate((mc.SWEEP_FORWARD, mc.SWEEP_BACKWARD)):
+        spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd, sweep=sweep)
+        cap = torch.cuda.Stream()
+        cap.wait_stream(H.stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap):
+            mc.fused_step_ex(I.L, I.tsets[j], order, g.data_ptr(), st["wset"], st["vset"], spec,
+                             int(torch.cuda.current_stream().cuda_stream))
+        torch.cuda.synchronize()
+        graphs.append(graph)
+    for i in range(warmup):
+        graphs[i % 2].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        graphs[(warmup + i) % 2].replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    bytes_ = 4 * (cfg.P + 5) * cfg.total
+    return {"ms_per_step": round(ms, 4), "GBps": round(bytes_ / ms / 1e6, 1),
+            "what": "two captured graphs (forward sweep on set 0, backward sweep on set 1) replayed alternately"}
+
+
+def flat_yardsticks(H, L, cfg, order, warmup, steps):
+    """mc_reduce_update on flat buffers, launched back to back on its own: the step's arithmetic and
+    access mix with no per-layer lookups at all (one fetch from the argument block per tile), i.e. what
+    the fused step would reach if finding its tensors cost nothing.  Warm: one state set; cold: weights,
+    momentum and g rotate over sets that exceed the memory-side cache, streaming state policy."""
+    mc, torch = H.mc, H.torch
+    N, P = cfg.total, cfg.P
+    n_x = max(3, int(np.ceil(1.2e9 / (4 * N * P))))
+    n_state = max(4, int(np.ceil(3 * CACHE_BYTES / (8 * N))))
+    n_g = max(4, int(np.ceil(3 * CACHE_BYTES / (4 * N))))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl_seed())
+    xs = [[torch.randn(N, device="cuda", generator=gen) * 1e-3 for _ in range(P)] for _ in range(n_x)]
+    ws = [torch.randn(N, device="cuda", generator=gen) * 0.05 for _ in range(n_state)]
+    vs = [torch.zeros(N, device="cuda") for _ in range(n_state)]
+    gs = [torch.empty(N, device="cuda") for _ in range(n_g)]
+    tabs = [[t.data_ptr() for t in x] for x in xs]
+    bytes_ = 4 * (P + 5) * N
+    out = {"kernel": kernel_names(mc, L, P, cfg.k)[1], "bytes_per_launch": bytes_,
+           "what": "mc_reduce_update alone on flat buffers (no per-layer lookups), random data"}
+    for name, policy, rotate in (("back_to_back", mc.STATE_RESIDENT, False), ("cold", mc.STATE_STREAMING, True)):
+        spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd, state_policy=policy, sweep=mc.SWEEP_FORWARD)
+
+        def launch(i):
+            s_ = i % n_state if rotate else 0
+            mc.reduce_update_ex(L, tabs[i % n_x], order, gs[i % n_g if rotate else 0].data_ptr(),
+                                ws[s_].data_ptr(), vs[s_].data_ptr(), spec, H.sh)
+        _, ev = H.time_region(launch, warmup, steps)
+        out[name] = {"kernel_ms": round(ev, 4), "GBps": round(bytes_ / ev / 1e6, 1),
+                     "frac": round(bytes_ / ev / 1e6 / HBM_PEAK_GBPS, 4)}
+    del xs, ws, vs, gs
+    torch.cuda.empty_cache()
+    return out
+
+
+def wl_seed():
+    return 171100705 + 424242
+
+
 def run_other_workload(H, name, order_kind, check_parity):
     """Fused step of one of the non-headline configurations: first step against the oracle, then
     W warm-up + K timed back-to-back steps over rotating contribution sets."""
@@ -320,6 +389,8 @@ def run_other_workload(H, name, order_kind, check_parity):
                 if state_bytes > CACHE_BYTES else
                 ("weights + momentum (%d MB) stay cache-resident between back-to-back steps" % (state_bytes >> 20)),
                 "setup_s": round(setup_s, 1)})
+    if state_bytes > CACHE_BYTES and n_sets == 2:
+        out["graph_replay"] = replayed_pair(H, I, order, g, st, cfg, W, K)
     if name != "tiny":
         cold, states, gs = cold_pass(H, I, order, K, W)
         out["cold"] = cold
@@ -807,6 +878,8 @@ def main():
         # free the headline's buffers before the large configurations
         del I, tables, tsets, flats, flat_table, w, v, g, fst, fw_layers, fv_layers, fw_set, fv_set, w_layers, w_table
         torch.cuda.empty_cache()
+        progress(f"{cfg.name}: the flat kernel alone, back to back and cold")
+        out["flat_kernel_yardstick"] = flat_yardsticks(H, L, cfg, order, args.warmup, args.steps)
         for name in WORKLOADS:
             if name != cfg.name:
                 others[name] = run_other_workload(H, name, args.order, check_parity=not args.no_cpu_baseline)
