@@ -260,7 +260,7 @@ int mc_fused_step(mc_layout* L, const mc_tensor_set* const* contrib, int32_t P, 
                   float lr, float mu, float wd, void* stream);
 
 /* ---- variants of the update: run-time hyper-parameters, Nesterov, the LR schedule ---------
- * Section 5 ("Experimental setup"): the learning rate starts at 0.1, is ramped linearly to
+ * Section 5 (the experimental setup): the learning rate starts at 0.1, is ramped linearly to
  * 0.1*k*n/256 (k = batch per GPU, n = number of workers), and is divided by 10 after every 30
  * epochs of a 90-epoch run.  The rate therefore changes from step to step, while a step captured
  * into a HIP graph replays fixed kernel arguments: the `_ex` entry points can read {lr, mu, wd}
