@@ -305,6 +305,42 @@ def replayed_pair(H, I, order, g, st, cfg, warmup, steps):
             "what": "two captured graphs (forward sweep on set 0, backward sweep on set 1) replayed alternately"}
 
 
+def staggered_arenas(H, I, order, g, st, cfg, warmup, steps, apart_bytes=4096):
+    """The same steps with every operand set (each contribution, weights, momentum) copied into one
+    arena of its own, the arenas' first tensors 4 KB apart in address phase.  When nothing of the state
+    fits the cache, all P + 2 streams of a tile come from HBM at once, and where they sit relative to
+    one another decides how many of them meet in the same DRAM bank: tensors allocated one by one put
+    every large tensor on a 2 MB boundary, i.e. all operands of a tile in the same phase."""
+    mc, torch = H.mc, H.torch
+    N, P = cfg.total, cfg.P
+    pad = apart_bytes // 4
+    keep = []
+
+    def arena_copy(q, layers):
+        arena = torch.empty(N + (P + 3) * pad, dtype=torch.float32, device="cuda")
+        keep.append(arena)
+        views, o = [], q * pad
+        for t in layers:
+            v = arena[o:o + t.numel()]
+            v.copy_(t)
+            views.append(v)
+            o += t.numel()
+        return mc.TensorSet(I.L, [v.data_ptr() if v.numel() else None for v in views])
+
+    tsets = [mc.set_table([arena_copy(p, I.dev_sets[s][p]) for p in range(P)]) for s in range(I.n_sets)]
+    wset, vset = arena_copy(P, st["w"]), arena_copy(P + 1, st["v"])
+
+    def step(i):
+        mc.fused_step(I.L, tsets[i % I.n_sets], order, g.data_ptr(), wset, vset, cfg.lr, cfg.mu, cfg.wd, H.sh)
+    wall, ev = H.time_region(step, warmup, steps)
+    bytes_ = 4 * (P + 5) * N
+    del tsets, wset, vset, keep
+    torch.cuda.empty_cache()
+    return {"ms_per_step": round(wall, 4), "kernel_ms": round(ev, 4), "GBps": round(bytes_ / wall / 1e6, 1),
+            "frac": round(bytes_ / ev / 1e6 / HBM_PEAK_GBPS, 4),
+            "what": f"each operand set in one arena, arenas {apart_bytes} B apart in address phase"}
+
+
 def flat_yardsticks(H, L, cfg, order, warmup, steps):
     """mc_reduce_update on flat buffers, launched back to back on its own: the step's arithmetic and
     access mix with no per-layer lookups at all (one fetch from the argument block per tile), i.e. what
@@ -391,6 +427,7 @@ def run_other_workload(H, name, order_kind, check_parity):
                 "setup_s": round(setup_s, 1)})
     if state_bytes > CACHE_BYTES and n_sets == 2:
         out["graph_replay"] = replayed_pair(H, I, order, g, st, cfg, W, K)
+        out["operands_in_staggered_arenas"] = staggered_arenas(H, I, order, g, st, cfg, W, K)
     if name != "tiny":
         cold, states, gs = cold_pass(H, I, order, K, W)
         out["cold"] = cold
