@@ -83,3 +83,12 @@ def test_no_table_beyond_32_colours_or_without_elements():
     assert mc.Layout([1000] * 40, 33).units()[0] == 0
     assert mc.Layout([0, 0], 2).units()[0] == 0
     assert mc.Layout([1000] * 40, 32).units()[0] > 0
+
+
+def test_units_query_rejects_missing_arguments():
+    import ctypes
+    L = mc.Layout([1000, 24], 2)
+    upc = ctypes.c_int32(-5)
+    assert mc.lib.mc_layout_units(None, ctypes.byref(upc), None, None) == mc.ERR_INVALID_ARG
+    assert mc.lib.mc_layout_units(L.handle, None, None, None) == mc.ERR_INVALID_ARG
+    assert mc.lib.mc_layout_units(L.handle, ctypes.byref(upc), None, None) == mc.OK and upc.value > 0
