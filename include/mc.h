@@ -421,7 +421,8 @@ enum {
                                       compute unit and so the number of loads in flight; -1 (default)
                                       = by the call: 16 wavefronts per compute unit when weights and
                                       momentum are expected in the memory-side cache, 12 when they
-                                      are streamed, 8 when they exceed the cache; 0 = no cap */
+                                      are streamed (payloads of 16 M elements and more), 8 when
+                                      they exceed the cache; 0 = no cap */
     MC_OPT_LDS_CAP_PACK = 11       /* the same for pack, unpack and mc_copy; default 0 (no cap) */
 };
 int mc_set_option(int option, int value);

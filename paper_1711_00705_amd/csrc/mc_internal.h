@@ -121,7 +121,8 @@ Shape shape_for(int64_t elems, int n_terms, bool stream_state);
 // kernels (update_lds_reservation) goes by the cache regime of the call, measured on the fused step:
 //   weights and momentum expected in the memory-side cache (resident policy, state that fits):
 //     16 per compute unit (10 KB per 64 threads); 12 loses 3 points there, 8 loses 7;
-//   streamed state that would fit (a cold step): 12 per compute unit (13 KB), +1 point over 16;
+//   streamed state that would fit (a cold step): 12 per compute unit (13 KB), +1 point over 16 --
+//     from 16 M elements up; a GoogLeNet-sized launch keeps 16 (12 costs it 1.5 points);
 //   state larger than the cache (VGG-16): 8 per compute unit (20 KB), +6-7 points over 16.
 // lds_reservation serves the copy-shaped kernels (MC_OPT_LDS_CAP_PACK; they only lose with a cap:
 // default none) and returns an explicit MC_OPT_LDS_CAP_UPDATE setting as it is; `threads` per

@@ -56,11 +56,12 @@ unsigned update_lds_reservation(const mc_layout* L, int threads, bool stream_sta
     if (v >= 0) return unsigned(v);
     // automatic.  The more of a step's traffic comes from HBM itself, the fewer wavefronts it wants:
     // weights and momentum expected in the memory-side cache: 16 per compute unit; streamed state
-    // (nothing cached): 12; state larger than the cache: 8.
+    // (nothing cached): 12, unless the payload is small (a GoogLeNet-sized launch is over after a few
+    // rounds of wavefronts and loses 1.5 points with fewer of them); state larger than the cache: 8.
     int per_wave = 10240;
     if (L->N * 8 > kMemorySideCacheBytes)
         per_wave = 20480;
-    else if (stream_state)
+    else if (stream_state && L->N >= (int64_t(1) << 24))
         per_wave = 13312;
     const int bytes = per_wave * (threads / 64);
     return unsigned(bytes < 65536 ? bytes : 65536);   // (64 KB is the most a launch may ask for)
