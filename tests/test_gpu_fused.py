@@ -183,6 +183,25 @@ def test_full_size_fused(name, order_kind):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("how", [0, 1, 2])
+def test_googlenet_under_every_work_mapping(how):
+    """GoogLeNet's many small, oddly sized tensors through the three ways a workgroup finds its work
+    (searched table, tensor-aligned units, flat tiles): the same bits every time."""
+    cfg = wl.workload("googlenet")
+    keep = mc.get_option(mc.OPT_DIRECT_TILES)
+    mc.set_option(mc.OPT_DIRECT_TILES, how)
+    try:
+        print(f"fused googlenet, work mapping {how}", flush=True)
+        st = gh.FusedStep(cfg.sizes, cfg.k)
+        xs = [wl.contribution_tensors(cfg.sizes, p) for p in range(cfg.P)]
+        gpu, ref = st.run(xs, wl.weight_tensors(cfg.sizes), wl.zero_tensors(cfg.sizes), cfg.lr, cfg.mu, cfg.wd,
+                          order=wl.rotation_order(cfg.k, cfg.P), misalign=[0])
+        st.check(gpu, ref, f"fused googlenet mapping {how}")
+    finally:
+        mc.set_option(mc.OPT_DIRECT_TILES, keep)
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("bump", [1, 2, 3])
 def test_full_size_odd_layout(bump):
     """ResNet-50's tensors each `bump` elements longer: every flat offset after the first tensor
