@@ -58,11 +58,11 @@ def csrc_digest():
     return h.hexdigest()[:16]
 
 
-def traffic_from_profile(kernel, workload, P, k):
+def traffic_from_profile(kernel, workload, P, k, suffix=""):
     """HBM-side bytes per launch of the dominant kernel from the rocprofv3 counter runs whose
     summary is kept under profiles/ -- or None when there is no summary for this kernel and
     workload, or when the kernel sources have changed since it was taken."""
-    path = os.path.join(ROOT, "profiles", f"{kernel.replace('_kernel', '')}_{workload}_P{P}_k{k}.txt")
+    path = os.path.join(ROOT, "profiles", f"{kernel.replace('_kernel', '')}_{workload}_P{P}_k{k}{suffix}.txt")
     traffic = digest = None
     try:
         for line in open(path):
@@ -904,8 +904,10 @@ def main():
     }
     if cold is not None:
         c = cold["streaming"]
+        cold_traffic, cold_src = traffic_from_profile(fused_kernel, cfg.name, P, k, "_cold")
         out["roofline_cold"] = {"bound": "hbm", "kernel": fused_kernel, "achieved": c["GBps"],
                                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": c["frac"],
+                                "traffic": cold_traffic, "traffic_source": cold_src,
                                 "bytes_per_launch": kernel_bytes, "kernel_ms": c["kernel_ms"],
                                 "ms_per_step": c["ms_per_step"], "state_policy": "streaming",
                                 "resident_policy": cold["resident"],
