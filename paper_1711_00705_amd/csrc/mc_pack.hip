@@ -23,10 +23,10 @@
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kMaxVecPerThread = int(mc::kPackTileElems / 4 / kThreads);  // 16-byte vectors per thread
-static_assert(mc::kPackTileElems == int64_t(kThreads) * 4 * kMaxVecPerThread, "tile shape");
-static_assert(kMaxVecPerThread == 2, "the launch code below instantiates V = 1 and V = 2");
+constexpr int kThreads = 64;
+constexpr int kVecPerThread = int(mc::kPackTileElems / 4 / kThreads);  // 16-byte vectors per thread
+static_assert(mc::kPackTileElems == int64_t(kThreads) * 4 * kVecPerThread, "tile shape");
+static_assert(kVecPerThread == 1, "the launch code below instantiates V = 1");
 
 struct PtrBatch {
     void* p[mc::kPackMaxPtrs];
@@ -169,9 +169,8 @@ int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch&
     const int64_t lo = L->off[t0], hi = L->off[t1];
     if (lo == hi) return MC_OK;
     const int nt = mc::option(MC_OPT_PACK_NONTEMPORAL);
-    // Small payloads use the finer tile so that the grid still fills the chip evenly.
-    const int vec = L->N / mc::kPackTileElems >= 8192 ? 2 : 1;
-    const int64_t tile_elems = int64_t(kThreads) * 4 * vec;
+    const int64_t tile_elems = mc::kPackTileElems;
+    const bool small = L->N < (int64_t(1) << 24);
     const int64_t tile0 = lo / tile_elems;
     const int64_t tile_end = (hi + tile_elems - 1) / tile_elems;
     if (tile_end - tile0 > 0x7fffffff) return MC_ERR_INVALID_ARG;
@@ -182,24 +181,17 @@ int launch_range(const mc_layout* L, const mc::DeviceTables* dt, const PtrBatch&
     // most tiles cutting through a cache line at a tensor boundary); large ones are indifferent,
     // and unpack, which often re-reads what an update has just written, loses with it.
     int xcd_run = mc::option(UNPACK ? MC_OPT_XCD_RUN_UNPACK : MC_OPT_XCD_RUN_PACK);
-    if (xcd_run < 0) xcd_run = (!UNPACK && vec == 1) ? 16 : 0;
+    if (xcd_run < 0) xcd_run = (!UNPACK && small) ? 16 : 0;
     const unsigned lds = mc::lds_reservation(MC_OPT_LDS_CAP_PACK, kThreads);
 #define MC_GS_LAUNCH_V(NT_T, NT_F, V, TABLE)                                                                  \
     hipLaunchKernelGGL((gather_scatter_kernel<UNPACK, NT_T, NT_F, V, TABLE>), grid, block, lds, s, table, dt->off, \
                        dt->tile_first, f, tile0, hi, t0, xcd_run, lo, batch)
-#define MC_GS_LAUNCH(NT_T, NT_F)                                   \
-    do {                                                           \
-        if (vec == 2) {                                            \
-            if (table)                                             \
-                MC_GS_LAUNCH_V(NT_T, NT_F, 2, true);               \
-            else                                                   \
-                MC_GS_LAUNCH_V(NT_T, NT_F, 2, false);              \
-        } else {                                                   \
-            if (table)                                             \
-                MC_GS_LAUNCH_V(NT_T, NT_F, 1, true);               \
-            else                                                   \
-                MC_GS_LAUNCH_V(NT_T, NT_F, 1, false);              \
-        }                                                          \
+#define MC_GS_LAUNCH(NT_T, NT_F)                               \
+    do {                                                       \
+        if (table)                                             \
+            MC_GS_LAUNCH_V(NT_T, NT_F, kVecPerThread, true);   \
+        else                                                   \
+            MC_GS_LAUNCH_V(NT_T, NT_F, kVecPerThread, false);  \
     } while (0)
     switch (nt & 3) {
         case 0: MC_GS_LAUNCH(false, false); break;

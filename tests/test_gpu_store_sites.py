@@ -1,7 +1,8 @@
 """Regression guard for the 128-bit write-through store (csrc/mc_mem.h): every kernel that issues
-it, in both tile shapes, on a payload large enough to take the two-vector shapes (>= 8192 tiles of
-2048 elements) yet small enough to check in a second.  A store whose data registers are rewritten
-too early shows up as scattered wrong words, so every word is compared."""
+it, in every workgroup shape it is built in (the update kernels' optional two-vector shape included),
+on a payload of 16.8 M elements: large enough for the large-payload choices of the launch code, small
+enough to check in a second.  A store whose data registers are rewritten too early shows up as
+scattered wrong words, so every word is compared."""
 import numpy as np
 import pytest
 
@@ -13,7 +14,7 @@ import oracle  # noqa: E402
 from paper_1711_00705_amd import mc  # noqa: E402
 import gpu_harness as gh  # noqa: E402
 
-SIZES = [9_000_000, 64, 7_800_000, 1000, 36]        # 16,801,100 elements: 8204 tiles of 2048
+SIZES = [9_000_000, 64, 7_800_000, 1000, 36]        # 16,801,100 elements, just above 2^24
 OPTS = (mc.OPT_RU_SHAPE, mc.OPT_STATE_POLICY, mc.OPT_STATE_STORE_SC1, mc.OPT_PACK_NONTEMPORAL)
 
 
@@ -34,7 +35,7 @@ def _words(n, salt):
 def test_pack_unpack_and_copy_store_sites():
     L = mc.Layout(SIZES, 4)
     O = oracle.Layout(SIZES, 4)
-    assert L.N // 2048 >= 8192
+    assert L.N >= 1 << 24
     host = [_words(s, 17 * t) for t, s in enumerate(SIZES)]
     dev, _ = gh.place_tensors(host)
     s = gh.stream_handle()
@@ -53,7 +54,7 @@ def test_pack_unpack_and_copy_store_sites():
     mc.copy(dst.data_ptr(), flat.data_ptr(), n_bytes, s)
     torch.cuda.synchronize()
     gh.assert_bits(dst[:n_bytes // 4].cpu().numpy(), flat[:n_bytes // 4].cpu().numpy(), "mc_copy")
-    small = mc.Layout([300_000, 12, 70_000], 2)             # one-vector shape of pack / unpack
+    small = mc.Layout([300_000, 12, 70_000], 2)             # a small payload (the launch code's other branch)
     hs = [_words(s_, 5 + t) for t, s_ in enumerate([300_000, 12, 70_000])]
     ds, _ = gh.place_tensors(hs)
     mc.set_option(mc.OPT_PACK_NONTEMPORAL, 3)
