@@ -419,10 +419,10 @@ enum {
     MC_OPT_LDS_CAP_UPDATE = 10,    /* bytes of unused LDS reserved per workgroup of reduce_update and
                                       fused_step (0..65536), which caps the workgroups resident per
                                       compute unit and so the number of loads in flight; -1 (default)
-                                      = by the call: 16 wavefronts per compute unit when weights and
-                                      momentum are expected in the memory-side cache, 12 when they
-                                      are streamed (payloads of 16 M elements and more), 8 when
-                                      they exceed the cache; 0 = no cap */
+                                      = by the call: none while weights and momentum are expected in
+                                      the memory-side cache, otherwise as many wavefronts per compute
+                                      unit as keep about 80 KB of loads in flight (14 for four
+                                      contributions, 8 for eight); 0 = no cap */
     MC_OPT_LDS_CAP_PACK = 11       /* the same for pack, unpack and mc_copy; default 0 (no cap) */
 };
 int mc_set_option(int option, int value);

@@ -948,8 +948,12 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
     // Only the plain whole-payload step alternates by itself: role calls come several to a step.
     a.reverse = mc::sweep_reversed(L, (n_terms && plan.sweep == MC_SWEEP_AUTO) ? MC_SWEEP_FORWARD : plan.sweep, ss) ? 1 : 0;
     a.xcd_run = mc::option(MC_OPT_XCD_RUN);
-    a.lds_per_wave = mc::update_lds_reservation(L, 64, ss);
-    a.lds_per_4waves = mc::update_lds_reservation(L, 256, ss);
+    {
+        const int avg_terms = uniform ? int(terms(first_active)) : 0;
+        const bool state_cached = !ss && !any_sum_only;
+        a.lds_per_wave = mc::update_lds_reservation(L, 64, state_cached, avg_terms, true);
+        a.lds_per_4waves = mc::update_lds_reservation(L, 256, state_cached, avg_terms, true);
+    }
     a.w = weights ? reinterpret_cast<float* const*>(weights->d_ptrs) : nullptr;
     a.v = momentum ? reinterpret_cast<float* const*>(momentum->d_ptrs) : nullptr;
     a.g = static_cast<float*>(grad_out);

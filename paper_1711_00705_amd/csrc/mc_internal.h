@@ -120,17 +120,22 @@ Shape shape_for(int64_t elems, int n_terms, bool stream_state);
 // VGG-16 size, +2-3 % warm.  How few wavefronts a real kernel tolerates depends on how long each
 // one sits on lookups before its first load (two batches of scalar loads in the fused step, one in
 // reduce_update) and on where the traffic comes from, so the automatic setting of the update
-// kernels (update_lds_reservation) goes by the cache regime of the call, measured on the fused step:
-//   weights and momentum expected in the memory-side cache (resident policy, state that fits):
-//     16 per compute unit (10 KB per 64 threads); 12 loses 3 points there, 8 loses 7;
-//   streamed state that would fit (a cold step): 12 per compute unit (13 KB), +1 point over 16 --
-//     from 16 M elements up; a GoogLeNet-sized launch keeps 16 (12 costs it 1.5 points);
-//   state larger than the cache (VGG-16): 8 per compute unit (20 KB), +6-7 points over 16.
+// kernels (update_lds_reservation) goes by the cache regime of the call.  Measured on the fused
+// step (% of the 8 TB/s peak; wavefronts per compute unit 32 / 16 / 14 / 12 / 10 / 8):
+//   ResNet-50, P = 4, back to back (state cache-resident)  89.3 / 89.0 / 87.2 / 84.7 / 82.6 / 80.7
+//   ResNet-50, P = 4, cold                                 79.4 / 80.2 / 80.9 / 79.1 / 76.7 / 74.2
+//   ResNet-50, P = 8, cold                                 75.7 / 74.5 / 75.9 / 78.0 / 78.5 / 78.7
+//   GoogLeNet, P = 4, cold                                 74.4 / 74.9 / 75.2 / 72.9 / 71.9 / 69.4
+//   VGG-16, P = 4 (state larger than the cache)            79.3 / 80.9 / 81.8 / 82.3 / 81.2 / 79.7
+// i.e. nothing to gain while the state is cached, and otherwise a constant amount of loads in flight:
+// 14 wavefronts x 6 KB, 8 x 10 KB, 12 x 6 KB.
 // lds_reservation serves the copy-shaped kernels (MC_OPT_LDS_CAP_PACK; they only lose with a cap:
 // default none) and returns an explicit MC_OPT_LDS_CAP_UPDATE setting as it is; `threads` per
 // workgroup of the launch.
 unsigned lds_reservation(int which, int threads);
-unsigned update_lds_reservation(const mc_layout* L, int threads, bool stream_state);
+// state_cached: every colour of the call updates, with the resident policy; terms: contributions per
+// colour, 0 for a launch whose colours differ in term count or update flag.
+unsigned update_lds_reservation(const mc_layout* L, int threads, bool state_cached, int terms, bool per_layer);
 
 // Cache treatment of weights and momentum for a call on layout L: `policy` is the caller's
 // MC_STATE_* value (MC_STATE_DEFAULT defers to MC_OPT_STATE_POLICY).  The library cannot know

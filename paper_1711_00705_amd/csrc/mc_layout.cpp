@@ -51,18 +51,25 @@ unsigned lds_reservation(int which, int threads) {
     return unsigned(v);
 }
 
-unsigned update_lds_reservation(const mc_layout* L, int threads, bool stream_state) {
+unsigned update_lds_reservation(const mc_layout* L, int threads, bool state_cached, int terms, bool per_layer) {
     const int v = g_lds_cap_update.load(std::memory_order_relaxed);
     if (v >= 0) return unsigned(v);
-    // automatic.  The more of a step's traffic comes from HBM itself, the fewer wavefronts it wants:
-    // weights and momentum expected in the memory-side cache: 16 per compute unit; streamed state
-    // (nothing cached): 12, unless the payload is small (a GoogLeNet-sized launch is over after a few
-    // rounds of wavefronts and loses 1.5 points with fewer of them); state larger than the cache: 8.
-    int per_wave = 10240;
-    if (L->N * 8 > kMemorySideCacheBytes)
-        per_wave = 20480;
-    else if (stream_state && L->N >= (int64_t(1) << 24))
-        per_wave = 13312;
+    // automatic.  Weights and momentum expected in the memory-side cache (every colour updates, resident
+    // policy, state that fits): no cap.  Otherwise (nearly) every stream of a tile comes from HBM, and
+    // what the step wants is a fixed amount of loads in flight per compute unit -- about 84 KB for the
+    // fused step, 72 KB when the state exceeds the cache or the buffers are flat (no per-layer lookups
+    // in front of the loads) -- so the number of wavefronts follows from the (terms + 2) KB each of
+    // them keeps in flight.
+    // (A launch whose colours differ in term count or update flag runs the general kernel, which sits
+    // on a longer chain of argument fetches: 16 wavefronts measured best for it, 10 lose 10 %.)
+    if (terms <= 0) return unsigned(10240 * (threads / 64));
+    const bool big = L->N * 8 > kMemorySideCacheBytes;
+    if (!big && state_cached) return 0;
+    const int kb = (big || !per_layer) ? 72 : 84;
+    int waves = (kb + (terms + 2) / 2) / (terms + 2);
+    if (waves < 4) waves = 4;
+    if (waves >= 32) return 0;
+    const int per_wave = (160 * 1024 / waves) / 1024 * 1024;   // LDS of a compute unit / wavefronts, in whole KB
     const int bytes = per_wave * (threads / 64);
     return unsigned(bytes < 65536 ? bytes : 65536);   // (64 KB is the most a launch may ask for)
 }

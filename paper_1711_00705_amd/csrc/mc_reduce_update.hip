@@ -273,8 +273,12 @@ int run_impl(const mc_layout* L, const void* const* contrib, int32_t P, const in
     const bool whole = !n_terms && r_lo == 0 && r_hi == L->N;
     a.reverse = mc::sweep_reversed(L, whole ? plan.sweep : (plan.sweep == MC_SWEEP_AUTO ? MC_SWEEP_FORWARD : plan.sweep), ss) ? 1 : 0;
     a.xcd_run = mc::option(MC_OPT_XCD_RUN);
-    a.lds_per_wave = mc::update_lds_reservation(L, 64, ss);
-    a.lds_per_4waves = mc::update_lds_reservation(L, 256, ss);
+    {
+        const int avg_terms = uniform ? int(terms(first_active)) : 0;
+        const bool state_cached = !ss && !any_sum_only;
+        a.lds_per_wave = mc::update_lds_reservation(L, 64, state_cached, avg_terms, false);
+        a.lds_per_4waves = mc::update_lds_reservation(L, 256, state_cached, avg_terms, false);
+    }
     a.g = static_cast<float*>(grad_out);
     a.w = static_cast<float*>(weights);
     a.v = static_cast<float*>(momentum);
