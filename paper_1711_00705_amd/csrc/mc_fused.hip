@@ -5,12 +5,17 @@
 // The flat index space (and with it the colour chunks and each colour's summation sequence) is
 // exactly that of pack + reduce_update + unpack: element i of the payload is element
 // i - off[t] of tensor t.  A tensor set is the device-resident list of one tensor pointer per
-// layer.  Workgroups walk colour segments in tiles; a tile that lies inside one tensor with
-// every operand 16-byte aligned (almost all tiles of a CNN payload) resolves its P + 2 base
-// pointers once and then runs the same 128-bit streaming loop as reduce_update; any other tile
-// takes a per-vector path that looks tensors up as it goes.  Tiles whose operands share a non-zero
-// offset from a 16-byte boundary (everything after an odd-sized tensor) shift their vectors to the
-// operands' boundary instead and store only g word by word.
+// layer.  Three kernels, chosen by the host:
+//   fused_unit_kernel    the default: one wavefront per tensor-aligned unit of the layout (a run of 256
+//                        elements counted from its tensor's first element), compile-time term count;
+//   fused_direct_kernel  flat 256-element tiles, a tile's colour found by division (layouts without a
+//                        unit table, MC_OPT_DIRECT_TILES = 2);
+//   fused_step_kernel    the general one: run-time term counts (9..32), per-colour roles, the
+//                        256-thread shape, colour segments searched in a per-launch table.
+// In all of them a work item that lies inside one tensor with every operand 16-byte aligned (almost
+// all of a CNN payload) resolves its P + 2 base pointers once and runs the same 128-bit streaming
+// body as reduce_update; anything else (a tensor's end, a colour bound, unaligned operands) takes a
+// masked or per-element path.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -577,10 +582,12 @@ __device__ __forceinline__ void partial_unit(const float* const* const* xs, cons
 // the flat gradient is reached at the tensor's flat offset.  (With flat tiles, one tensor whose length
 // is not a multiple of 32 elements leaves every later tile's P + 2 tensor-side accesses straddling
 // cache lines that the neighbouring tile, on another die, fetches again: GoogLeNet's step took 4 %
-// longer for it, and a ResNet-50-sized payload split in two at an offset of 4 elements 5 %.)  Lookups come in two batches, as in fused_direct_kernel:
+// longer for it, and a ResNet-50-sized payload split in two at an offset of 4 elements 5 %.)
+// The eight scalars in front of the argument block arrive in registers when the wavefront starts
+// (kernel-argument preload); the lookups then come in two batches, as in fused_direct_kernel:
 // (1) the slot's tensor, and from the argument block the colour's P pointer tables, the chunk length
-// and the hyper-parameters; (2) the tensor's bounds, the index of its first unit in
-// the colour, and the P + 2 operand addresses.
+// and the hyper-parameters; (2) the tensor's bounds, the index of its first unit in the colour, and
+// the P + 2 operand addresses.
 // flip: index of the last slot when the launch walks backwards, -1 otherwise.
 template <int P, int MODE, bool SS>
 __global__ __launch_bounds__(64) void fused_unit_kernel(const int32_t* __restrict__ unit_tensor,

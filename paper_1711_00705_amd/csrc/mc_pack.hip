@@ -9,7 +9,8 @@
 // Device pointers of the tensors travel in the kernel-argument block (no staging copy, no
 // synchronisation); a layout with more tensors than fit is processed in several launches.  The
 // `_set` forms read the pointers from a tensor set's device table instead: one launch whatever
-// the number of tensors.
+// the number of tensors.  One wavefront per workgroup and one vector per thread: a tile is 256
+// flat elements, the granularity of the layout's lookup table.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -3,9 +3,12 @@
 // The pass is pure streaming: per element it reads P + 2 words and writes 2 or 3, with P + 4
 // flops, so it is bound by HBM bandwidth and the kernel's only job is to keep enough 128-bit
 // loads in flight.  The grid is partitioned by colour: each colour owns a contiguous run of
-// workgroups (a prefix table in the kernel arguments maps blockIdx -> colour), and the
-// colour's summation sequence is applied by handing that colour its own, already permuted,
-// list of contribution pointers.  Colours never synchronise with each other (Section 4.2).
+// workgroups, and the colour's summation sequence is applied by handing that colour its own,
+// already permuted, list of contribution pointers.  Colours never synchronise with each other
+// (Section 4.2).  Two kernels: reduce_update_direct_kernel (the usual launch: 256-element tiles,
+// a tile's colour found by dividing its index by the chunk length, compile-time term count) and
+// reduce_update_kernel (run-time term counts, per-colour roles, the 256-thread shape, and calls
+// whose colours do not fit one launch: a prefix table in the kernel arguments maps blockIdx -> colour).
 //
 // Arithmetic is written operation by operation and the file is compiled with floating-point
 // contraction off, so each add and multiply is rounded once to binary32 exactly as in the
