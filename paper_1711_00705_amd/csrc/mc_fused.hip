@@ -183,19 +183,65 @@ __device__ __forceinline__ void uniform_tile(const float* const* xp, const float
             }
         }
     } else {
+        // Up to kFirst terms (the counts a tree rank meets that have no compile-time body: 5, 6, 7
+        // contributions) have their addresses looked up together and their loads issued together, each
+        // guarded by a uniform test of the run-time count.  Larger counts load the first term, then
+        // four at a time.  The adds run strictly left to right either way.
+        constexpr int kFirst = U == 1 ? 8 : 4;
+        int q;
+        if (np <= kFirst) {
+            const float* xq0[kFirst];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (on[u]) {
-                if (UPDATE) {
-                    wv[u] = mc::load_state<SS>(wp + j[u]);
-                    vv[u] = mc::load_state<SS>(vp + j[u]);
-                }
-                acc[u] = load4<true>(xs[0][t0] + rel + j[u]);
+            for (int r = 0; r < kFirst; ++r) {
+                xq0[r] = nullptr;
+                if (r < np) xq0[r] = xs[r][t0] + rel;
             }
+            float4 first[kFirst][U];
+#pragma unroll
+            for (int r = 0; r < kFirst; ++r) {
+                if (r < np) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (on[u]) first[r][u] = load4<true>(xq0[r] + j[u]);
+                }
+            }
+            if (UPDATE) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (on[u]) {
+                        wv[u] = mc::load_state<SS>(wp + j[u]);
+                        vv[u] = mc::load_state<SS>(vp + j[u]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u] = first[0][u];
+#pragma unroll
+            for (int r = 1; r < kFirst; ++r) {
+                if (r < np) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        acc[u].x = acc[u].x + first[r][u].x;
+                        acc[u].y = acc[u].y + first[r][u].y;
+                        acc[u].z = acc[u].z + first[r][u].z;
+                        acc[u].w = acc[u].w + first[r][u].w;
+                    }
+                }
+            }
+            q = np;
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (on[u]) {
+                    if (UPDATE) {
+                        wv[u] = mc::load_state<SS>(wp + j[u]);
+                        vv[u] = mc::load_state<SS>(vp + j[u]);
+                    }
+                    acc[u] = load4<true>(xs[0][t0] + rel + j[u]);
+                }
+            }
+            q = 1;
         }
-        // Four terms' loads are issued before their adds (more bytes in flight); the adds still
-        // run strictly left to right.
-        int q = 1;
         for (; q + 4 <= np; q += 4) {
             float4 t[4][U];
 #pragma unroll
