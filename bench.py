@@ -509,16 +509,26 @@ def cpu_baseline(cfg, order, host_sets, w_layers_host, seconds, parity_ref, gpu_
     }
 
 
-def roles_experiment(H, L, cfg, flats, g, w, v, n_nodes, reps):
+def roles_experiment(H, L, cfg, flats, g, w, v, n_nodes, reps, I=None, wset=None, vset=None):
     """One rank's real share in a k-colour tree Allreduce over n_nodes nodes (Section 4.2): it
     is inner node or root of at most one colour and a leaf of the others.  Phase 1: per colour,
     add the m local replicas (leaf) or those plus one buffer per child (inner node, root); only
     the root's colour is updated at once -- one launch whatever the mix.  Phase 2: the other colours
     are updated from the broadcast sum (a single contribution).  m = the workload's P; child
     buffers are further flat buffers of the same size.  Times both phases for one rank of each
-    kind, with the algorithmic bytes of each."""
+    kind, with the algorithmic bytes of each -- on flat buffers (mc_reduce_update_roles) and, given the
+    per-layer inputs, on per-layer tensors (mc_fused_step_ex with the same roles)."""
     torch, mc = H.torch, H.mc
     N, m, k = cfg.total, cfg.P, cfg.k
+    fused_sets = fused_bcast = None
+    if I is not None and I.n_sets >= 3 and k <= len(I.dev_sets[1]):
+        def tset(layers):
+            return mc.TensorSet(L, [t.data_ptr() if t.numel() else None for t in layers])
+        keep_sets = [tset(I.dev_sets[0][p]) for p in range(m)] + [tset(I.dev_sets[1][c]) for c in range(k)]
+        fused_sets = mc.set_table(keep_sets)
+        keep_bcast = [tset(I.dev_sets[2][0])]
+        fused_bcast = mc.set_table(keep_bcast)
+        spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd)
     bounds = [int(b) for b in L.colour_bounds()]
     lens = [bounds[c + 1] - bounds[c] for c in range(k)]
     child_bufs = [torch.randn(N, dtype=torch.float32, device="cuda") * 1e-3 for _ in range(k)]
@@ -552,6 +562,14 @@ def roles_experiment(H, L, cfg, flats, g, w, v, n_nodes, reps):
                               "sum_ms": round(t1, 4), "sum_GBps": round(bytes1 / t1 / 1e6, 1),
                               "update_from_broadcast_ms": round(t2, 4),
                               "update_GBps": round(bytes2 / t2 / 1e6, 1) if t2 else None}
+        if fused_sets is not None:
+            f1 = timed(lambda: mc.fused_step_ex(L, fused_sets, None, g.data_ptr(), wset, vset, spec, H.sh,
+                                                n_terms=n_terms, do_update=upd))
+            f2 = timed(lambda: mc.fused_step_ex(L, fused_bcast, None, None, wset, vset, spec, H.sh,
+                                                n_terms=later, do_update=[1] * k)) if any(later) else 0.0
+            out["ranks"][kind].update({"per_layer_sum_ms": round(f1, 4), "per_layer_sum_GBps": round(bytes1 / f1 / 1e6, 1),
+                                       "per_layer_update_from_broadcast_ms": round(f2, 4),
+                                       "per_layer_update_GBps": round(bytes2 / f2 / 1e6, 1) if f2 else None})
     return out
 
 
@@ -845,7 +863,8 @@ def main():
     if not args.only_headline:
         progress(f"{cfg.name}: roles and cold-state passes")
         if args.roles_nodes > 0 and k * ((args.roles_nodes - 1 + k - 1) // k) <= args.roles_nodes:
-            roles = roles_experiment(H, L, cfg, flats, g, w, v, args.roles_nodes, reps=max(5, min(args.steps, 30)))
+            roles = roles_experiment(H, L, cfg, flats, g, w, v, args.roles_nodes, reps=max(5, min(args.steps, 30)),
+                                     I=I, wset=fw_set, vset=fv_set)
         if True:
             cold, states, gs = cold_pass(H, I, order, args.steps, args.warmup)
             del states, gs

@@ -736,6 +736,153 @@ __global__ __launch_bounds__(64) void fused_unit_kernel(const int32_t* __restric
     }
 }
 
+// One unit of a colour with a run-time term count np (1..8): the body of fused_unit_roles_kernel.
+// Loads are guarded by uniform tests of np, so indexing stays static and nothing beyond the colour's
+// pointer list is touched.
+template <bool HAS_G, bool UPDATE, bool SS>
+__device__ __forceinline__ void roles_unit(const float* const* const* xs, int np, const float* const* xb, float* wb,
+                                           float* vb, float* const* w, float* const* v, float* g, int32_t t,
+                                           int64_t rel, int64_t blk_lo, int64_t e_lo, int64_t e_hi, bool aligned,
+                                           const mc::Hyper& hp) {
+    constexpr int kMost = 8;
+    const int64_t e = blk_lo + int64_t(threadIdx.x) * 4;   // flat index of the lane's first element
+    const int64_t r = rel + int64_t(threadIdx.x) * 4;      // the same element inside tensor t
+    const bool whole = (e_lo == blk_lo) & (e_hi == blk_lo + MC_COLOUR_ALIGN_ELEMS) & aligned;
+    if (whole || (aligned && e >= e_lo && e + 4 <= e_hi)) {
+        float4 term[kMost], wq, vq;
+#pragma unroll
+        for (int q = 0; q < kMost; ++q)
+            if (q < np) term[q] = load4<true>(xb[q] + r);
+        if (UPDATE) {
+            wq = mc::load_state<SS>(wb + r);
+            vq = mc::load_state<SS>(vb + r);
+        }
+        float4 acc = term[0];
+#pragma unroll
+        for (int q = 1; q < kMost; ++q) {
+            if (q < np) {
+                acc.x = acc.x + term[q].x;
+                acc.y = acc.y + term[q].y;
+                acc.z = acc.z + term[q].z;
+                acc.w = acc.w + term[q].w;
+            }
+        }
+        if (HAS_G) {
+            if ((blk_lo & 3) == 0) {
+                store4<true>(g + e, acc);
+            } else {
+                st1(g + e + 0, acc.x);
+                st1(g + e + 1, acc.y);
+                st1(g + e + 2, acc.z);
+                st1(g + e + 3, acc.w);
+            }
+        }
+        if (UPDATE) {
+            mc::sgd(acc.x, wq.x, vq.x, hp);
+            mc::sgd(acc.y, wq.y, vq.y, hp);
+            mc::sgd(acc.z, wq.z, vq.z, hp);
+            mc::sgd(acc.w, wq.w, vq.w, hp);
+            mc::store_state<SS>(wb + r, wq, hp.state_store_sc1);
+            mc::store_state<SS>(vb + r, vq, hp.state_store_sc1);
+        }
+        return;
+    }
+    for (int i = 0; i < 4; ++i) {
+        const int64_t ee = e + i;
+        if (ee >= e_lo && ee < e_hi) one_element<HAS_G, UPDATE>(xs, np, t, r + i, w, v, g, ee, hp);
+    }
+}
+
+// Tensor-aligned units for a launch whose colours differ in term count or update flag (a rank's
+// role-dependent step on per-layer tensors, Section 4.2), every count at most eight.  As
+// fused_unit_kernel, with one more fetch in front: the colour's descriptor word (first pointer slot,
+// term count, update flag) comes from the argument block before its pointer tables can be read.
+template <bool SS>
+__global__ __launch_bounds__(64) void fused_unit_roles_kernel(const int32_t* __restrict__ unit_tensor,
+                                                              const int32_t* __restrict__ unit_first,
+                                                              const int64_t* __restrict__ off, float* const* w,
+                                                              float* const* v, int32_t units_per_colour, int32_t flip,
+                                                              int64_t range_hi, FusedArgs a) {
+    constexpr int kUnit = MC_COLOUR_ALIGN_ELEMS;
+    constexpr int kMost = 8;
+    const int slot = flip >= 0 ? flip - int(blockIdx.x) : int(blockIdx.x);
+    const int c = int(uint32_t(slot) / uint32_t(units_per_colour));
+    const int local = slot - c * units_per_colour;
+    const uint32_t info = a.seg_info[c];
+    const int64_t chunk = a.chunk;
+    float* const g = a.g;
+    const mc::UpdateParams up = a.up;
+    const int32_t t_raw = unit_tensor[slot];
+    __builtin_amdgcn_sched_barrier(0);
+    const int np = int((info >> 16) & 0xffu);
+    if (np == 0 || t_raw < 0) return;                // a colour this call skips, or a padding slot
+    const bool update = ((info >> 24) & 1u) != 0;
+    const int32_t t = t_raw;
+    const float* const* const* xs = a.x + int(info & 0xffffu);
+    const float* const* xt[kMost];
+#pragma unroll
+    for (int q = 0; q < kMost; ++q) {
+        xt[q] = nullptr;
+        if (q < np) xt[q] = xs[q];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    typedef long long ll2 __attribute__((ext_vector_type(2)));
+    ll2 bounds;
+    __builtin_memcpy(&bounds, off + t, sizeof(bounds));
+    const int32_t first = unit_first[c + t];
+    const float* xb[kMost];
+#pragma unroll
+    for (int q = 0; q < kMost; ++q) {
+        xb[q] = nullptr;
+        if (q < np) xb[q] = xt[q][t];
+    }
+    float* wb = nullptr;
+    float* vb = nullptr;
+    if (update) {
+        wb = w[t];
+        vb = v[t];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const mc::Hyper hp = mc::resolve(up);
+
+    const int64_t c_lo = int64_t(c) * chunk;
+    const int64_t c_end = c_lo + chunk;
+    const int64_t c_hi = c_end < range_hi ? c_end : range_hi;
+    const int64_t lo = c_lo > bounds.x ? c_lo : bounds.x;
+    const int64_t hi = c_hi < bounds.y ? c_hi : bounds.y;
+    const int64_t j = ((lo - bounds.x) >> 8) + (local - first);
+    static_assert(kUnit == 256, "the shift above");
+    const int64_t rel = j * kUnit;
+    const int64_t blk_lo = bounds.x + rel;
+    const int64_t e_lo = blk_lo > lo ? blk_lo : lo;
+    const int64_t e_hi = blk_lo + kUnit < hi ? blk_lo + kUnit : hi;
+    uintptr_t low_bits = reinterpret_cast<uintptr_t>(wb) | reinterpret_cast<uintptr_t>(vb);
+#pragma unroll
+    for (int q = 0; q < kMost; ++q) low_bits |= reinterpret_cast<uintptr_t>(xb[q]);
+    const bool aligned = (low_bits & 15) == 0;
+    if (update) {
+        if (g)
+            roles_unit<true, true, SS>(xs, np, xb, wb, vb, w, v, g, t, rel, blk_lo, e_lo, e_hi, aligned, hp);
+        else
+            roles_unit<false, true, SS>(xs, np, xb, wb, vb, w, v, g, t, rel, blk_lo, e_lo, e_hi, aligned, hp);
+    } else {
+        roles_unit<true, false, SS>(xs, np, xb, wb, vb, w, v, g, t, rel, blk_lo, e_lo, e_hi, aligned, hp);
+    }
+}
+
+void launch_unit_roles(bool ss, hipStream_t s, const FusedArgs& a, const mc::DeviceTables* dt, int32_t units_per_colour,
+                       int32_t k) {
+    const unsigned blocks = unsigned(units_per_colour) * unsigned(k);
+    const dim3 grid(blocks), block(64);
+    const int32_t flip = a.reverse ? int32_t(blocks) - 1 : -1;
+    if (ss)
+        hipLaunchKernelGGL((fused_unit_roles_kernel<true>), grid, block, a.lds_per_wave, s, dt->unit_tensor, dt->unit_first,
+                           a.off, a.w, a.v, units_per_colour, flip, a.range_hi, a);
+    else
+        hipLaunchKernelGGL((fused_unit_roles_kernel<false>), grid, block, a.lds_per_wave, s, dt->unit_tensor, dt->unit_first,
+                           a.off, a.w, a.v, units_per_colour, flip, a.range_hi, a);
+}
+
 template <int P>
 void launch_unit_mode(int mode, bool ss, hipStream_t s, const FusedArgs& a, const mc::DeviceTables* dt,
                       int32_t units_per_colour, int32_t k) {
@@ -1056,7 +1203,12 @@ static int fused_run_impl(mc_layout* L, const mc_tensor_set* const* contrib, int
             }
         }
         if (per_segment) {
-            launch_per_segment(ss, unsigned(tiles_total), s, a);
+            if (max_terms <= 8 && a.xcd_run < 2 && dt->unit_tensor && mc::option(MC_OPT_DIRECT_TILES) == 1) {
+                a.chunk = L->chunk;
+                launch_unit_roles(ss, s, a, dt, L->units_per_colour, L->k);
+            } else {
+                launch_per_segment(ss, unsigned(tiles_total), s, a);
+            }
         } else {
             const int mode = !updates(first_active) ? kSumOnly : (a.g ? kUpdateAndG : kUpdateOnly);
             const bool few = terms(first_active) <= 8 && a.xcd_run < 2;   // (a run of tiles per die is the general kernel's)
