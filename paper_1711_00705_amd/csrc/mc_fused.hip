@@ -5,12 +5,14 @@
 // The flat index space (and with it the colour chunks and each colour's summation sequence) is
 // exactly that of pack + reduce_update + unpack: element i of the payload is element
 // i - off[t] of tensor t.  A tensor set is the device-resident list of one tensor pointer per
-// layer.  Three kernels, chosen by the host:
+// layer.  Four kernels, chosen by the host:
 //   fused_unit_kernel    the default: one wavefront per tensor-aligned unit of the layout (a run of 256
 //                        elements counted from its tensor's first element), compile-time term count;
+//   fused_unit_roles_kernel  the same units for calls whose colours differ in term count (up to
+//                        eight) or update flag: a rank's role-dependent step;
 //   fused_direct_kernel  flat 256-element tiles, a tile's colour found by division (layouts without a
 //                        unit table, MC_OPT_DIRECT_TILES = 2);
-//   fused_step_kernel    the general one: run-time term counts (9..32), per-colour roles, the
+//   fused_step_kernel    the general one: run-time term counts (9..32), roles with such counts, the
 //                        256-thread shape, colour segments searched in a per-launch table.
 // In all of them a work item that lies inside one tensor with every operand 16-byte aligned (almost
 // all of a CNN payload) resolves its P + 2 base pointers once and runs the same 128-bit streaming
