@@ -393,8 +393,8 @@ int mc_last_hip_error(void);           /* raw hipError_t of this thread's last M
 enum {
     MC_OPT_RU_SHAPE = 1,           /* workgroup shape of reduce_update and fused_step: 1 = 64 threads x
                                       one 16-byte vector, 2 = 256 threads x two vectors; 0 (default) =
-                                      chosen per launch from the size, the term count and the state
-                                      policy */
+                                      the library's choice (the one-wavefront shape: it measured
+                                      fastest or level on every configuration) */
     MC_OPT_STATE_POLICY = 2,       /* what MC_STATE_DEFAULT means: MC_STATE_RESIDENT (default) or
                                       MC_STATE_STREAMING */
     MC_OPT_PACK_NONTEMPORAL = 3,   /* pack/unpack: bit 0 streaming access to the per-layer
