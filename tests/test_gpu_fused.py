@@ -183,6 +183,24 @@ def test_full_size_fused(name, order_kind):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("k,misalign", [(32, None), (7, [1, 0, 3, 2, 0])])
+def test_thousands_of_tiny_tensors(k, misalign):
+    """Every unit is a partial one: 6000 tensors of 0..9 elements around two larger ones, up to the
+    largest colour count the unit table is built for."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    sizes = [int(x) for x in rng.integers(0, 10, size=6000)]
+    sizes[1234] = 70_001
+    sizes[4321] = 4096
+    P = 3
+    st = gh.FusedStep(sizes, k)
+    assert st.L.units()[0] > 0
+    xs = [wl.contribution_tensors(sizes, p) for p in range(P)]
+    w = wl.weight_tensors(sizes)
+    v = [rng.standard_normal(s, dtype=np.float32) * np.float32(0.01) for s in sizes]
+    gpu, ref = st.run(xs, w, v, 0.05, 0.9, 1e-4, order=wl.random_order(k, P, seed=3), misalign=misalign)
+    st.check(gpu, ref, f"tiny tensors k={k}")
+
+
 @pytest.mark.parametrize("how", [0, 1, 2])
 def test_googlenet_under_every_work_mapping(how):
     """GoogLeNet's many small, oddly sized tensors through the three ways a workgroup finds its work
