@@ -120,3 +120,53 @@ def test_full_size_roles_nesterov_device_hyper():
     gh.assert_bits(g.cpu().numpy(), gr, "g (roles)")
     gh.assert_bits(w.cpu().numpy(), wr, "w (roles)")
     gh.assert_bits(v.cpu().numpy(), vr, "v (roles)")
+
+
+def test_full_size_roles_on_per_layer_tensors():
+    """ResNet-50 size through mc_fused_step_ex with a rank's roles (the paper's 8-node, 4-colour
+    example, 4 local replicas): the root of colour 0 adds 8 buffers there and 4 elsewhere and updates
+    only its own colour; an inner node adds 7 and 4 and updates nothing; then the other colours are
+    updated from a broadcast sum.  State is carried from call to call and checked every time."""
+    cfg = wl.workload("resnet50")
+    k, m = cfg.k, cfg.P
+    P = m + k
+    L = mc.Layout(cfg.sizes, k)
+    O = oracle.Layout(cfg.sizes, k)
+    N = L.N
+    print(f"full size fused roles N={N} P={P} k={k}", flush=True)
+    rng = np.random.Generator(np.random.PCG64(23))
+    xs_layers = [wl.contribution_tensors(cfg.sizes, p) for p in range(P)]
+    xs_h = [oracle.pack(O, t) for t in xs_layers]
+    w_layers = wl.weight_tensors(cfg.sizes)
+    v_layers = [rng.standard_normal(s, dtype=np.float32) * np.float32(0.01) for s in cfg.sizes]
+    wr, vr = oracle.pack(O, w_layers), oracle.pack(O, v_layers)
+    gr = np.zeros(N, np.float32)
+    s = gh.stream_handle()
+    dev_x = [gh.place_tensors(t)[0] for t in xs_layers]
+    dev_w, _ = gh.place_tensors(w_layers)
+    dev_v, _ = gh.place_tensors(v_layers)
+    sets = mc.set_table([mc.TensorSet(L, gh.ptrs(d)) for d in dev_x])
+    wset, vset = mc.TensorSet(L, gh.ptrs(dev_w)), mc.TensorSet(L, gh.ptrs(dev_v))
+    g = gh.dev_empty(N, fill=0)
+    spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd)
+
+    def check(what):
+        torch.cuda.synchronize()
+        gh.assert_bits(g.cpu().numpy(), gr, f"g ({what})")
+        for a, b in zip(dev_w, oracle.unpack(O, wr)):
+            gh.assert_bits(a.cpu().numpy(), b, f"w ({what})")
+        for a, b in zip(dev_v, oracle.unpack(O, vr)):
+            gh.assert_bits(a.cpu().numpy(), b, f"v ({what})")
+
+    for what, n_terms, do_update in (("root of colour 0", [8, 4, 4, 4], [1, 0, 0, 0]),
+                                     ("inner node of colour 0", [7, 4, 4, 4], [0, 0, 0, 0]),
+                                     ("two children here, one there", [6, 5, 4, 4], [0, 1, 0, 0])):
+        mc.fused_step_ex(L, sets, None, g.data_ptr(), wset, vset, spec, s, n_terms=n_terms, do_update=do_update)
+        oracle.reduce_update_roles(O, xs_h, n_terms, do_update, gr, wr, vr, cfg.lr, cfg.mu, cfg.wd)
+        check(what)
+    # the non-root colours updated from a broadcast sum (one contribution), colour 0 skipped
+    bcast = mc.set_table([mc.TensorSet(L, gh.ptrs(dev_x[5]))])
+    mc.fused_step_ex(L, bcast, None, g.data_ptr(), wset, vset, spec, s, n_terms=[0, 1, 1, 1], do_update=[1, 1, 1, 1])
+    oracle.reduce_update_roles(O, [xs_h[5]], [0, 1, 1, 1], [1, 1, 1, 1], gr, wr, vr, cfg.lr, cfg.mu, cfg.wd)
+    check("update from a broadcast sum")
+    torch.cuda.empty_cache()
