@@ -174,6 +174,42 @@ def test_pack_unpack_identity_coded_and_guards():
         assert np.array_equal(after[~touched], before[~touched]), "unpack wrote outside its tensors"
 
 
+@pytest.mark.parametrize("mis", [[0], [1], [2], [3], [3, 1, 2]])
+def test_shifted_tensors_many_whole_tiles(mis):
+    """Tensors of many tiles whose addresses sit 1, 2 or 3 elements off the 16-byte grid relative
+    to their flat offsets (every combination: the odd sizes shift the offsets too): the tiles
+    move as realigned vectors, the first and last tile of each tensor element by element.  Word
+    j of tensor t holds off_t + j; nothing outside the tensors may change."""
+    sizes = [1, 3000, 2, 2050, 5, 777, 4099, 1280, 256, 260, 263, 515]
+    L = mc.Layout(sizes, 4)
+    N = L.N
+    ts, run = [], 0
+    for s in sizes:
+        ts.append(np.arange(run, run + s, dtype=np.uint32).view(np.float32))
+        run += s
+    print(f"shifted tensors mis={mis} N={N}", flush=True)
+    dts, _arena = gh.place_tensors(ts, mis)
+    G = 64
+    buf = gh.dev_empty(N + 2 * G)
+    flat = buf[G:G + N]
+    mc.pack(L, gh.ptrs(dts), flat.data_ptr(), gh.stream_handle())
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy().view(np.uint32)
+    assert np.all(host[:G] == 0xFFFFFFFF) and np.all(host[G + N:] == 0xFFFFFFFF), "pack wrote outside flat"
+    assert np.array_equal(host[G:G + N], np.arange(N, dtype=np.uint32))
+    outs, arena2 = gh.place_tensors([np.zeros(s, np.float32) for s in sizes], mis)
+    before = arena2.cpu().numpy().view(np.uint32).copy()
+    mc.unpack(L, flat.data_ptr(), gh.ptrs(outs), gh.stream_handle())
+    torch.cuda.synchronize()
+    after = arena2.cpu().numpy().view(np.uint32)
+    touched = np.zeros(after.size, bool)
+    for o, t in zip(outs, ts):
+        lo = (o.data_ptr() - arena2.data_ptr()) // 4
+        touched[lo:lo + t.size] = True
+        gh.assert_bits(o.cpu().numpy(), t, "unpack")
+    assert np.array_equal(after[~touched], before[~touched]), "unpack wrote outside its tensors"
+
+
 def test_arbitrary_bit_patterns_survive_pack_unpack():
     sizes = [1000, 37, 5000, 2]
     L = mc.Layout(sizes, 2)
