@@ -322,7 +322,9 @@ int mc_hyper_write(float* hyper_dev, float lr, float mu, float wd, void* stream)
  * a copy kernel, a peer GPU, a network adapter -- writes the data into the contribution buffer
  * first and then raises the flag with release semantics at device scope.  Two ways are provided:
  * mc_packet_deliver copies n_elems fp32 from src to dst (device, 16-byte aligned, not overlapping)
- * and adds to *flag the number of elements written, workgroup by workgroup;  mc_packet_signal stores a
+ * and then, from a second launch behind the copy, adds n_elems to *flag once (a writer should touch
+ * the polled word once per delivery: an add per workgroup of the copy serialises on it and is
+ * slowed further by every poller);  mc_packet_signal stores a
  * value into ready[packet] from a kernel on `stream`, i.e. after everything queued there before it.
  *
  * Every wait is bounded: a workgroup polls at most spin_limit times in total (half a microsecond to
