@@ -305,6 +305,34 @@ def replayed_pair(H, I, order, g, st, cfg, warmup, steps):
             "what": "two captured graphs (forward sweep on set 0, backward sweep on set 1) replayed alternately"}
 
 
+def replayed_chain(H, I, order, g, st, cfg, n_sets, chain=20, reps=10):
+    """A launch-bound step (microseconds of work) as a caller would run it in a loop: `chain`
+    consecutive steps over the rotating contribution sets captured into ONE graph, which is then
+    replayed; per-step time of the replays against the same steps launched one by one."""
+    mc, torch = H.mc, H.torch
+    spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd, sweep=mc.SWEEP_FORWARD)
+    cap = torch.cuda.Stream()
+    cap.wait_stream(H.stream)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=cap):
+        sh = int(torch.cuda.current_stream().cuda_stream)
+        for j in range(chain):
+            mc.fused_step_ex(I.L, I.tsets[j % n_sets], order, g.data_ptr(), st["wset"], st["vset"], spec, sh)
+    torch.cuda.synchronize()
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / (reps * chain)
+    bytes_ = 4 * (cfg.P + 5) * cfg.total
+    return {"ms_per_step": round(ms, 5), "GBps": round(bytes_ / ms / 1e6, 1),
+            "what": f"{chain} consecutive steps captured into one graph, {reps} replays"}
+
+
 def staggered_arenas(H, I, order, g, st, cfg, warmup, steps, apart_bytes=4096):
     """The same steps with every operand set (each contribution, weights, momentum) copied into one
     arena of its own, the arenas' first tensors 4 KB apart in address phase.  When nothing of the state
@@ -428,6 +456,8 @@ def run_other_workload(H, name, order_kind, check_parity):
     if state_bytes > CACHE_BYTES and n_sets == 2:
         out["graph_replay"] = replayed_pair(H, I, order, g, st, cfg, W, K)
         out["operands_in_staggered_arenas"] = staggered_arenas(H, I, order, g, st, cfg, W, K)
+    if name == "tiny":
+        out["graph_replay"] = replayed_chain(H, I, order, g, st, cfg, n_sets)
     if name != "tiny":
         cold, states, gs = cold_pass(H, I, order, K, W)
         out["cold"] = cold
