@@ -170,3 +170,70 @@ def test_full_size_roles_on_per_layer_tensors():
     oracle.reduce_update_roles(O, [xs_h[5]], [0, 1, 1, 1], [1, 1, 1, 1], gr, wr, vr, cfg.lr, cfg.mu, cfg.wd)
     check("update from a broadcast sum")
     torch.cuda.empty_cache()
+
+
+def test_full_size_packet_pipeline_two_steps():
+    """The packet pipeline as bench.py drives it, at ResNet-50 size: two of the four contributions
+    land in 16 packets (colours interleaved) on a second stream, paced by mc_delay, while one
+    resident reducer of 256 workgroups sums each packet when its flag is complete; then the ordered
+    second call.  Two steps in a row (flags and progress reset in between, state carried)."""
+    cfg = wl.workload("resnet50")
+    k, P = cfg.k, cfg.P
+    L = mc.Layout(cfg.sizes, k)
+    O = oracle.Layout(cfg.sizes, k)
+    N = L.N
+    order = wl.rotation_order(k, P)
+    n_blocks = 256
+    bounds = [int(b) for b in L.colour_bounds()]
+    per_colour = []
+    for c in range(k):
+        lo, hi = bounds[c], bounds[c + 1]
+        step = -(-(-(-(hi - lo) // 4)) // 256) * 256
+        per_colour.append([(b, min(hi, b + step)) for b in range(lo, hi, step)])
+    pk = [p[j] for j in range(max(len(p) for p in per_colour)) for p in per_colour if j < len(p)]
+    print(f"full size packet pipeline N={N} packets={len(pk)}", flush=True)
+    pk_dev = torch.tensor(np.array(pk, dtype=np.int64).reshape(-1), device="cuda")
+    ready = torch.zeros(len(pk), dtype=torch.int32, device="cuda")
+    progress = torch.zeros(n_blocks + mc.PACKETS_STATUS_WORDS, dtype=torch.int32, device="cuda")
+    main, prod = torch.cuda.current_stream(), torch.cuda.Stream()
+    s, ps = int(main.cuda_stream), int(prod.cuda_stream)
+    arriving = [2, 3]
+    w_h = oracle.pack(O, wl.weight_tensors(cfg.sizes))
+    v_h = np.zeros(N, np.float32)
+    w, v, g = gh.to_dev(w_h), gh.to_dev(v_h), gh.dev_empty(N)
+    spec = mc.update_spec(cfg.lr, cfg.mu, cfg.wd)
+    x_dev = [gh.dev_empty(N) for _ in range(P)]
+    for step_no in range(2):
+        xs_h = [oracle.pack(O, wl.contribution_tensors(cfg.sizes, p, step=step_no)) for p in range(P)]
+        src = {p: gh.to_dev(xs_h[p]) for p in arriving}
+        for p in range(P):
+            if p in arriving:
+                x_dev[p].view(torch.int32).fill_(-1)          # NaN canaries until the packets land
+            else:
+                x_dev[p].copy_(torch.from_numpy(xs_h[p]))
+        torch.cuda.synchronize()
+
+        def reducer():
+            mc.reduce_update_packets(L, [x.data_ptr() for x in x_dev], order, g.data_ptr(), w.data_ptr(), v.data_ptr(),
+                                     spec, pk_dev.data_ptr(), len(pk), ready.data_ptr(), len(arriving), 200000,
+                                     progress.data_ptr(), n_blocks, s)
+        mc.packets_reset(ready.data_ptr(), len(pk), progress.data_ptr(), n_blocks, s)
+        prod.wait_stream(main)
+        reducer()
+        for j, (b, e) in enumerate(pk):
+            mc.delay(20, ps)
+            for p in arriving:
+                mc.packet_deliver(x_dev[p].data_ptr() + 4 * b, src[p].data_ptr() + 4 * b, e - b,
+                                  ready.data_ptr() + 4 * j, ps)
+        done = torch.cuda.Event()
+        done.record(prod)
+        main.wait_event(done)
+        reducer()
+        torch.cuda.synchronize()
+        pr = progress.cpu().numpy()
+        assert np.all(pr[:n_blocks] == len(pk)) and pr[n_blocks + 1] == 0, f"step {step_no}: not every packet done"
+        print(f"step {step_no}: workgroups that gave up in the first call: {int(pr[n_blocks])}", flush=True)
+        g_ref = oracle.reduce_update(O, xs_h, w_h, v_h, cfg.lr, cfg.mu, cfg.wd, order=order)
+        gh.assert_bits(g.cpu().numpy(), g_ref, f"step {step_no}: g")
+        gh.assert_bits(w.cpu().numpy(), w_h, f"step {step_no}: w")
+        gh.assert_bits(v.cpu().numpy(), v_h, f"step {step_no}: v")
