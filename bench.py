@@ -631,7 +631,7 @@ def pipeline_experiment(H, L, cfg, order, flats, flat_table, g, w, v, packets, r
         pk.append([(b, min(hi, b + step)) for b in range(lo, hi, step)])
     order_of_packets = [p[j] for j in range(max(len(p) for p in pk)) for p in pk if j < len(p)]
     n_pk = len(order_of_packets)
-    n_blocks = blocks
+    n_blocks = min(blocks, 2 * torch.cuda.get_device_properties(0).multi_processor_count)   # the entry point's limit
     pk_dev = torch.tensor(np.array(order_of_packets, dtype=np.int64).reshape(-1), device="cuda")
     ready = torch.zeros(n_pk, dtype=torch.int32, device="cuda")
     progress_dev = torch.zeros(n_blocks + mc.PACKETS_STATUS_WORDS, dtype=torch.int32, device="cuda")

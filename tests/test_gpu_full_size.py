@@ -183,7 +183,7 @@ def test_full_size_packet_pipeline_two_steps():
     O = oracle.Layout(cfg.sizes, k)
     N = L.N
     order = wl.rotation_order(k, P)
-    n_blocks = 256
+    n_blocks = min(256, 2 * torch.cuda.get_device_properties(0).multi_processor_count)
     bounds = [int(b) for b in L.colour_bounds()]
     per_colour = []
     for c in range(k):

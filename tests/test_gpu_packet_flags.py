@@ -20,7 +20,8 @@ import gpu_harness as gh  # noqa: E402
 SIZES = [700_000, 36, 1_500_000, 4097, 800_001]      # 3,004,135 elements, ragged end
 K, P = 4, 4
 LR, MU, WD = 0.1, 0.9, 1e-4
-N_BLOCKS = 512
+# twice the compute units is the most the entry point accepts (512 on a whole MI355X)
+N_BLOCKS = min(512, 2 * torch.cuda.get_device_properties(0).multi_processor_count) if torch.cuda.is_available() else 512
 
 
 def _packets(bounds, packet_elems):

@@ -55,6 +55,7 @@ def test_random_packets(seed):
             b = e
     pk = [pk[i] for i in rng.permutation(len(pk))]
     n_blocks = int(rng.choice([1, 7, 64, 256, 512]))
+    n_blocks = min(n_blocks, 2 * torch.cuda.get_device_properties(0).multi_processor_count)   # the entry point's limit
     deliver = bool(rng.integers(0, 2)) and P >= 2
     lr, mu, wd = 0.1, 0.9, 1e-4
     print(f"random packets {seed}: n={len(sizes)} N={N} k={k} P={P} packets={len(pk)} blocks={n_blocks} "
